@@ -1,0 +1,112 @@
+"""ctypes front end of the fp64 C oracle (oracle/attn_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the
+benchmark's cpu_baseline leg.  Arrays are numpy float64, row-major, shaped
+[..., N, D]; leading axes are flattened into independent heads.  The
+arithmetic lives in the C file, whose header states the definition it follows
+(paper Figure 1 listing plus the temperature of the Appendix B.3 listing;
+backward by the chain rule).
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        lib = ctypes.CDLL(path)
+        dp = ctypes.POINTER(ctypes.c_double)
+        lp = ctypes.POINTER(ctypes.c_long)
+        L, I, F = ctypes.c_long, ctypes.c_int, ctypes.c_double
+        lib.oracle_attn_fwd.argtypes = [dp, dp, dp, dp, dp, dp, L, L, L, I, F]
+        lib.oracle_attn_fwd_rows.argtypes = [dp, dp, dp, lp, L, dp, dp, L, L, I, F]
+        lib.oracle_attn_bwd.argtypes = [dp, dp, dp, dp, dp, dp, dp, dp, dp, L, L, L, I, F]
+        lib.oracle_attn_ds.argtypes = [dp, dp, dp, dp, dp, L, L, L, I, F]
+        for f in (lib.oracle_attn_fwd, lib.oracle_attn_fwd_rows, lib.oracle_attn_bwd,
+                  lib.oracle_attn_ds, lib.oracle_num_threads):
+            f.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _c(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _heads(q, k, v):
+    if q.shape != k.shape or q.shape != v.shape or q.ndim < 2:
+        raise ValueError("q, k, v must share a shape [..., N, D]")
+    N, D = q.shape[-2:]
+    BH = int(np.prod(q.shape[:-2], dtype=np.int64)) if q.ndim > 2 else 1
+    return BH, N, D
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def attn_fwd(q, k, v, causal: bool, scale: float, return_p: bool = False):
+    """O [..., N, D], LSE [..., N] (and P [..., N, N] if return_p), all float64."""
+    BH, N, D = _heads(q, k, v)
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v)
+    o = np.empty(q.shape, np.float64)
+    lse = np.empty(q.shape[:-1], np.float64)
+    p = np.empty(q.shape[:-1] + (N,), np.float64) if return_p else None
+    rc = _load().oracle_attn_fwd(qp, kp, vp, _c(o)[1], _c(lse)[1],
+                                 _c(p)[1] if return_p else None, BH, N, D, int(causal), float(scale))
+    if rc:
+        raise RuntimeError(f"oracle_attn_fwd failed: {rc}")
+    return (o, lse, p) if return_p else (o, lse)
+
+
+def attn_fwd_rows(q, k, v, rows, causal: bool, scale: float):
+    """Selected query rows of ONE head: q, k, v are [N, D]; returns O [len(rows), D], LSE [len(rows)]."""
+    BH, N, D = _heads(q, k, v)
+    if BH != 1:
+        raise ValueError("attn_fwd_rows takes one head")
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    o = np.empty((len(rows), D), np.float64)
+    lse = np.empty((len(rows),), np.float64)
+    rc = _load().oracle_attn_fwd_rows(qp, kp, vp, rows.ctypes.data_as(ctypes.POINTER(ctypes.c_long)),
+                                      len(rows), _c(o)[1], _c(lse)[1], N, D, int(causal), float(scale))
+    if rc:
+        raise RuntimeError(f"oracle_attn_fwd_rows failed: {rc}")
+    return o, lse
+
+
+def attn_bwd(q, k, v, d_o, causal: bool, scale: float, return_stats: bool = False):
+    """dQ, dK, dV [..., N, D] float64 (and Delta, LSE [..., N] if return_stats)."""
+    BH, N, D = _heads(q, k, v)
+    if d_o.shape != q.shape:
+        raise ValueError("d_o must have q's shape")
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v); d_o, dop = _c(d_o)
+    dq = np.empty(q.shape, np.float64)
+    dk = np.empty(q.shape, np.float64)
+    dv = np.empty(q.shape, np.float64)
+    delta = np.empty(q.shape[:-1], np.float64)
+    lse = np.empty(q.shape[:-1], np.float64)
+    rc = _load().oracle_attn_bwd(qp, kp, vp, dop, _c(dq)[1], _c(dk)[1], _c(dv)[1],
+                                 _c(delta)[1], _c(lse)[1], BH, N, D, int(causal), float(scale))
+    if rc:
+        raise RuntimeError(f"oracle_attn_bwd failed: {rc}")
+    return (dq, dk, dv, delta, lse) if return_stats else (dq, dk, dv)
+
+
+def attn_ds(q, k, v, d_o, causal: bool, scale: float):
+    """dS [..., N, N] float64 (tiny shapes; for invariant tests)."""
+    BH, N, D = _heads(q, k, v)
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v); d_o, dop = _c(d_o)
+    ds = np.empty(q.shape[:-1] + (N,), np.float64)
+    rc = _load().oracle_attn_ds(qp, kp, vp, dop, _c(ds)[1], BH, N, D, int(causal), float(scale))
+    if rc:
+        raise RuntimeError(f"oracle_attn_ds failed: {rc}")
+    return ds
