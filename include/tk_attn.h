@@ -1,0 +1,115 @@
+/*
+ * tk_attn.h - C ABI of the MI355X (gfx950) fused exact softmax attention library.
+ *
+ * The operation is the attention of the paper's Figure 1 (PyTorch listing:
+ * softmax(Q K^T) V, softmax in fp32, probabilities cast to bf16 before the
+ * second product) with the 1/sqrt(D) temperature that the Appendix B.3
+ * listing folds into a base-2 exponent, an optional causal mask, and the
+ * per-row log-sum-exp as a second output.  The backward pass is its
+ * gradient; the paper reports only its speed (Section 4.1, Table 3), so the
+ * algorithm is the chain rule with P recomputed from the saved LSE.
+ *
+ * Conventions common to every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, to
+ *     contiguous row-major memory, 16-byte aligned.  Q, K, V, O, dO, dQ, dK,
+ *     dV are bf16 [B, H, N, D]; LSE is fp32 [B, H, N].
+ *   - D is 64 or 128.  N is a positive multiple of 128.  B, H >= 1 and
+ *     B*H*ceil(N/128) must fit a 31-bit grid.
+ *   - scale must be finite and > 0 (the running maximum is taken on raw
+ *     scores, which is only the maximum of the scaled scores for scale > 0).
+ *   - causal != 0 masks keys j > i (the diagonal is kept).
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work: no allocation, no free, no host
+ *     synchronisation, no global state.  Outputs are fully overwritten.
+ *   - Inputs and outputs must not alias.
+ *   - Return value: TK_OK (0) or a negative TK_ERR_* code.  Arguments are
+ *     validated on the host before any HIP call is made, so every error
+ *     except TK_ERR_LAUNCH is reported without touching the GPU.
+ */
+#ifndef TK_ATTN_H
+#define TK_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    TK_OK = 0,
+    TK_ERR_NULL_PTR = -1,            /* a required pointer is NULL */
+    TK_ERR_BAD_DIM = -2,             /* D not in {64,128}, N not a positive multiple of 128, B or H < 1, grid overflow */
+    TK_ERR_MISALIGNED = -3,          /* a tensor pointer is not 16-byte aligned */
+    TK_ERR_BAD_SCALE = -4,           /* scale is not finite or not > 0 */
+    TK_ERR_WORKSPACE_TOO_SMALL = -5, /* workspace_bytes < tk_attn_bwd_workspace_bytes(...) */
+    TK_ERR_LAUNCH = -6               /* hipGetLastError() reported a failure after a launch */
+};
+
+/*
+ * Forward pass (Figure 1 listing; Appendix B.3 listing for the streaming
+ * form: running max and sum per query row, base-2 exponent with the folded
+ * temperature, rescale of the output accumulator, normalisation at the end).
+ *
+ *   S_ij  = scale * sum_d Q_id K_jd          (keys j <= i only when causal)
+ *   P_ij  = exp(S_ij - LSE_i),  LSE_i = ln sum_j exp(S_ij)
+ *   O_id  = sum_j P_ij V_jd
+ *
+ * q, k, v : in,  bf16 [B,H,N,D]
+ * o       : out, bf16 [B,H,N,D]  (fp32 accumulation, one round-to-nearest-even at the end)
+ * lse     : out, fp32 [B,H,N]    (natural log, of the SCALED scores)
+ */
+int tk_attn_fwd(const void* q, const void* k, const void* v,
+                void* o, float* lse,
+                int B, int H, int N, int D, int causal, float scale,
+                void* stream);
+
+/*
+ * Backward pass: gradients of L = sum(O * dO) with respect to Q, K, V.
+ *
+ *   Delta_i = sum_d dO_id O_id
+ *   P_ij    = exp(scale * Q_i.K_j - LSE_i)   (recomputed, never stored)
+ *   dV_jd   = sum_i P_ij dO_id
+ *   dP_ij   = sum_d dO_id V_jd
+ *   dS_ij   = P_ij (dP_ij - Delta_i)
+ *   dQ_id   = scale * sum_j dS_ij K_jd
+ *   dK_jd   = scale * sum_i dS_ij Q_id
+ *
+ * q, k, v, o, d_o : in, bf16 [B,H,N,D]; o and lse exactly as tk_attn_fwd wrote them
+ * lse             : in, fp32 [B,H,N]
+ * dq, dk, dv      : out, bf16 [B,H,N,D] (fp32 accumulation)
+ * workspace       : device scratch of at least tk_attn_bwd_workspace_bytes(B,H,N,D) bytes,
+ *                   16-byte aligned; holds Delta (fp32 [B,H,N]) and the fp32 dQ accumulator
+ *                   ([B,H,N,D]).  The library clears what it needs on the stream; contents
+ *                   after the call are unspecified.  Two calls that overlap in time must
+ *                   not share a workspace.
+ * dQ is accumulated with fp32 atomics across key tiles, so its low-order bits
+ * may differ from run to run; dK and dV are bit-reproducible.
+ */
+int tk_attn_bwd(const void* q, const void* k, const void* v,
+                const void* o, const void* d_o, const float* lse,
+                void* dq, void* dk, void* dv,
+                int B, int H, int N, int D, int causal, float scale,
+                void* workspace, size_t workspace_bytes,
+                void* stream);
+
+/* Bytes of workspace tk_attn_bwd needs for this shape; 0 if the shape is invalid. */
+size_t tk_attn_bwd_workspace_bytes(int B, int H, int N, int D);
+
+/*
+ * The first stage of the backward pass on its own: Delta_i = sum_d dO_id O_id.
+ * o, d_o : in, bf16 [B,H,N,D];  delta : out, fp32 [B,H,N].  (D, N rules as above.)
+ * Exposed so that its memory throughput can be measured separately.
+ */
+int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta,
+                      int B, int H, int N, int D, void* stream);
+
+/* Human-readable name of a status code (static storage; never NULL). */
+const char* tk_status_string(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int tk_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TK_ATTN_H */

@@ -1,0 +1,169 @@
+"""Thin Python binding of the C ABI in include/tk_attn.h (argument marshalling only).
+
+The functions named ``tk_*`` take torch CUDA tensors (used purely as device
+buffers) and forward pointers, sizes and the current HIP stream to the
+shared library; every step of the computation runs in the HIP kernels.
+There is no fallback: if the library is missing, loading raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtk_attn.so")
+
+TK_OK = 0
+TK_ERR_NULL_PTR = -1
+TK_ERR_BAD_DIM = -2
+TK_ERR_MISALIGNED = -3
+TK_ERR_BAD_SCALE = -4
+TK_ERR_WORKSPACE_TOO_SMALL = -5
+TK_ERR_LAUNCH = -6
+
+EXPORTS = ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
+           "tk_status_string", "tk_attn_version")
+
+_lib = None
+
+
+class TkAttnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
+    """Load libtk_attn.so (built by paper_2410_20399_amd/build.py). Raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} not found: build it with `python -m paper_2410_20399_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(path)
+    vp, fp, i, f, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.tk_attn_fwd.argtypes = [vp, vp, vp, vp, fp, i, i, i, i, i, f, vp]
+    lib.tk_attn_fwd.restype = i
+    lib.tk_attn_bwd.argtypes = [vp, vp, vp, vp, vp, fp, vp, vp, vp, i, i, i, i, i, f, vp, sz, vp]
+    lib.tk_attn_bwd.restype = i
+    lib.tk_attn_bwd_workspace_bytes.argtypes = [i, i, i, i]
+    lib.tk_attn_bwd_workspace_bytes.restype = sz
+    lib.tk_attn_bwd_delta.argtypes = [vp, vp, fp, i, i, i, i, vp]
+    lib.tk_attn_bwd_delta.restype = i
+    lib.tk_status_string.argtypes = [i]
+    lib.tk_status_string.restype = ctypes.c_char_p
+    lib.tk_attn_version.argtypes = []
+    lib.tk_attn_version.restype = i
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().tk_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load_library().tk_attn_version())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check_bf16(name, t, shape=None):
+    if not (t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous()):
+        raise ValueError(f"{name} must be a contiguous CUDA bf16 tensor")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {tuple(shape)}")
+
+
+def _check_f32(name, t, shape):
+    if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == tuple(shape)):
+        raise ValueError(f"{name} must be a contiguous CUDA fp32 tensor of shape {tuple(shape)}")
+
+
+# ------------------------------------------------------------------ the C ABI, same names
+def tk_attn_fwd(q, k, v, o, lse, B, H, N, D, causal, scale, stream=None) -> int:
+    return load_library().tk_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
+                                      B, H, N, D, int(bool(causal)), float(scale), _stream(stream))
+
+
+def tk_attn_bwd(q, k, v, o, d_o, lse, dq, dk, dv, B, H, N, D, causal, scale,
+                workspace, workspace_bytes, stream=None) -> int:
+    return load_library().tk_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse),
+                                      _ptr(dq), _ptr(dk), _ptr(dv), B, H, N, D, int(bool(causal)),
+                                      float(scale), _ptr(workspace), int(workspace_bytes), _stream(stream))
+
+
+def tk_attn_bwd_workspace_bytes(B, H, N, D) -> int:
+    return int(load_library().tk_attn_bwd_workspace_bytes(B, H, N, D))
+
+
+def tk_attn_bwd_delta(o, d_o, delta, B, H, N, D, stream=None) -> int:
+    return load_library().tk_attn_bwd_delta(_ptr(o), _ptr(d_o), _ptr(delta), B, H, N, D, _stream(stream))
+
+
+# ------------------------------------------------------------------ convenience: allocate outputs, raise on error
+def attn_fwd(q, k, v, causal: bool, scale: float, out=None, stream=None):
+    """q, k, v: CUDA bf16 [B,H,N,D]. Returns (o bf16 [B,H,N,D], lse fp32 [B,H,N])."""
+    _check_bf16("q", q)
+    B, H, N, D = q.shape
+    _check_bf16("k", k, q.shape)
+    _check_bf16("v", v, q.shape)
+    if out is None:
+        o = torch.empty_like(q)
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    else:
+        o, lse = out
+        _check_bf16("o", o, q.shape)
+        _check_f32("lse", lse, (B, H, N))
+    rc = tk_attn_fwd(q, k, v, o, lse, B, H, N, D, causal, scale, stream)
+    if rc != TK_OK:
+        raise TkAttnError(rc, "tk_attn_fwd")
+    return o, lse
+
+
+def alloc_bwd_workspace(B, H, N, D, device="cuda"):
+    nbytes = tk_attn_bwd_workspace_bytes(B, H, N, D)
+    if nbytes == 0:
+        raise TkAttnError(TK_ERR_BAD_DIM, "tk_attn_bwd_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def attn_bwd(q, k, v, o, d_o, lse, causal: bool, scale: float, workspace=None, out=None, stream=None):
+    """Returns (dq, dk, dv) bf16 [B,H,N,D]; o and lse must come from attn_fwd on the same inputs."""
+    _check_bf16("q", q)
+    B, H, N, D = q.shape
+    for name, t in (("k", k), ("v", v), ("o", o), ("d_o", d_o)):
+        _check_bf16(name, t, q.shape)
+    _check_f32("lse", lse, (B, H, N))
+    if workspace is None:
+        workspace = alloc_bwd_workspace(B, H, N, D, q.device)
+    if out is None:
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    else:
+        dq, dk, dv = out
+    rc = tk_attn_bwd(q, k, v, o, d_o, lse, dq, dk, dv, B, H, N, D, causal, scale,
+                     workspace, workspace.numel() * workspace.element_size(), stream)
+    if rc != TK_OK:
+        raise TkAttnError(rc, "tk_attn_bwd")
+    return dq, dk, dv
+
+
+def attn_bwd_delta(o, d_o, stream=None):
+    _check_bf16("o", o)
+    _check_bf16("d_o", d_o, o.shape)
+    B, H, N, D = o.shape
+    delta = torch.empty((B, H, N), dtype=torch.float32, device=o.device)
+    rc = tk_attn_bwd_delta(o, d_o, delta, B, H, N, D, stream)
+    if rc != TK_OK:
+        raise TkAttnError(rc, "tk_attn_bwd_delta")
+    return delta

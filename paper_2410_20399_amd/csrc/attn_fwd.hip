@@ -1,0 +1,253 @@
+// Fused exact softmax attention, forward pass, for gfx950 (MI355X).
+//
+// One workgroup = 4 waves = 128 query rows of one (batch, head); each wave owns 32 query rows.
+// K and V are streamed in tiles of 64 keys through a two-stage LDS ring filled by direct
+// global->LDS loads.  Per tile each wave computes, with v_mfma_f32_32x32x16_bf16:
+//
+//   S^T = K Q^T          (so that a lane owns ONE query: softmax statistics are lane-local)
+//   online softmax in base 2 with the temperature folded into the exponent
+//                        (the streaming recurrence of the paper's Appendix B.3 listing)
+//   O^T += V^T P^T       (P^T in accumulator layout IS a valid B operand; V^T comes from
+//                         row-major V in LDS through transposing reads)
+//
+// Epilogue: O = O / l -> bf16, LSE = m*scale + ln l.
+#include "tk_common.h"
+#include "tk_launch.h"
+
+namespace tk {
+
+template <int D>
+struct FwdShape {
+    static constexpr int kWaves = 4;
+    static constexpr int kThreads = kWaves * 64;
+    static constexpr int kTileQ = kWaves * 32;          // query rows per workgroup
+    static constexpr int kTileKV = 64;                  // keys per LDS stage
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kChunksPerRow = D / 8;         // 16-byte chunks
+    static constexpr int kTileBytes = kTileKV * kRowBytes;
+    static constexpr int kStageBytes = 2 * kTileBytes;  // K tile then V tile
+    static constexpr int kLdsBytes = 2 * kStageBytes;
+    static constexpr int kLoadsPerTile = kTileKV * kChunksPerRow / kThreads;  // per thread
+};
+
+// LDS layout of a [64 x D] bf16 tile: row-major, with the 16-byte chunk index XOR-ed by a
+// function of the row so that the two read patterns below spread over all 64 banks.
+//   K tile, read as MFMA A operand: 16 consecutive lanes read the same chunk of 16 consecutive rows.
+//   V tile, read through ds_read_b64_tr_b16: 32 lanes read a 4-row x 64-byte block.
+template <int D> __device__ __forceinline__ int swizzle_k(int row) {
+    return D == 128 ? (row & 15) : ((row >> 1) & 7);
+}
+template <int D> __device__ __forceinline__ int swizzle_v(int row) {
+    return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+}
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(256, 2)
+void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
+                     bf16* __restrict__ O, float* __restrict__ LSE,
+                     int N, int num_q_tiles, int total_wg, float scale)
+{
+    using S = FwdShape<D>;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int l32 = lane & 31;
+    const int h = lane >> 5;
+
+    // workgroup -> (head, query tile); heavy (late) query tiles first when causal
+    const int logical = xcd_remap(blockIdx.x, total_wg);
+    const int bh = logical / num_q_tiles;
+    int qt = logical % num_q_tiles;
+    if (CAUSAL) qt = num_q_tiles - 1 - qt;
+
+    const size_t head = (size_t)bh * N * D;
+    const bf16* Qh = Q + head;
+    const bf16* Kh = K + head;
+    const bf16* Vh = V + head;
+    const int q0 = qt * S::kTileQ + wave * 32;   // first query row of this wave
+    const int my_q = q0 + l32;
+
+    const float c = scale * kLog2e;              // base-2 temperature
+
+    // ---- Q fragments (B operand of S^T = K Q^T): lane holds Q[my_q][16*kb + 8*h .. +7]
+    bf16x8 qf[D / 16];
+#pragma unroll
+    for (int kb = 0; kb < D / 16; kb++)
+        qf[kb] = *(const bf16x8*)(Qh + (size_t)my_q * D + kb * 16 + h * 8);
+
+    // ---- per-thread source offsets of the direct-to-LDS tile loads
+    // LDS slot s = it*256 + tid holds (row = s / chunks_per_row, physical chunk = s % chunks_per_row).
+    int k_src[S::kLoadsPerTile], v_src[S::kLoadsPerTile];
+#pragma unroll
+    for (int it = 0; it < S::kLoadsPerTile; it++) {
+        int s = it * S::kThreads + tid;
+        int row = s / S::kChunksPerRow, pc = s % S::kChunksPerRow;
+        k_src[it] = row * D + ((pc ^ swizzle_k<D>(row)) * 8);
+        v_src[it] = row * D + ((pc ^ swizzle_v<D>(row)) * 8);
+    }
+    auto issue_tile = [&](int stage, int tile) {
+        const bf16* kt = Kh + (size_t)tile * S::kTileKV * D;
+        const bf16* vt = Vh + (size_t)tile * S::kTileKV * D;
+        char* base = smem + stage * S::kStageBytes + wave * 1024;
+#pragma unroll
+        for (int it = 0; it < S::kLoadsPerTile; it++)
+            load_global_to_lds16(kt + k_src[it], base + it * (S::kThreads * 16));
+#pragma unroll
+        for (int it = 0; it < S::kLoadsPerTile; it++)
+            load_global_to_lds16(vt + v_src[it], base + S::kTileBytes + it * (S::kThreads * 16));
+    };
+
+    // ---- per-lane LDS read offsets (the XOR with a compile-time chunk index is applied at use)
+    // K: row = 32*b + l32, logical chunk 2*kb + h
+    const int k_lane = l32 * S::kRowBytes + ((h ^ swizzle_k<D>(l32)) << 4);
+    // V (transposing read): 16-lane group G = lane/16 -> (d half = G%2, key half = G/2);
+    //   lane j of the group addresses row 4*(G/2) + j/4, columns 32*db + 16*(G%2) + 4*(j%4)
+    const int j16 = lane & 15;
+    const int v_row = 4 * h + (j16 >> 2);
+    const int v_chunk = 2 * ((lane >> 4) & 1) + ((j16 & 3) >> 1);
+    const int v_lane = v_row * S::kRowBytes + ((v_chunk ^ swizzle_v<D>(v_row)) << 4) + ((j16 & 1) << 3);
+
+    f32x16 o_acc[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; db++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) o_acc[db][r] = 0.f;
+    float m_run = -INFINITY;   // running max of raw scores (shared by both half-waves)
+    float l_run = 0.f;         // running sum, partial: this lane's 32 of the 64 keys per tile
+
+    auto compute_tile = [&](int stage, int tile) {
+        const int j0 = tile * S::kTileKV;
+        if (CAUSAL && j0 > q0 + 31) return;          // every key of the tile is masked for this wave
+        const char* ks = smem + stage * S::kStageBytes;
+        const char* vs = ks + S::kTileBytes;
+
+        // S^T[key][query] for two 32-key blocks
+        f32x16 s[2];
+#pragma unroll
+        for (int b = 0; b < 2; b++) {
+#pragma unroll
+            for (int r = 0; r < 16; r++) s[b][r] = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < D / 16; kb++) {
+                bf16x8 kf = lds_read_b128(ks, (k_lane ^ ((2 * kb) << 4)) + b * 32 * S::kRowBytes);
+                s[b] = mfma32(kf, qf[kb], s[b]);
+            }
+        }
+        if (CAUSAL && j0 + S::kTileKV - 1 > q0) {    // tile crosses the diagonal for some row of this wave
+#pragma unroll
+            for (int b = 0; b < 2; b++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    int key = j0 + 32 * b + 8 * (r >> 2) + 4 * h + (r & 3);
+                    if (key > my_q) s[b][r] = -INFINITY;
+                }
+        }
+        // running max
+        float mx = s[0][0];
+#pragma unroll
+        for (int r = 1; r < 16; r++) mx = __builtin_fmaxf(mx, s[0][r]);
+#pragma unroll
+        for (int r = 0; r < 16; r++) mx = __builtin_fmaxf(mx, s[1][r]);
+        mx = half_max(mx);
+        const float m_new = __builtin_fmaxf(m_run, mx);
+        const float mc = m_new * c;
+        const float corr = __builtin_amdgcn_exp2f(m_run * c - mc);
+        m_run = m_new;
+        // P = 2^(S*c - m*c), partial row sums
+        float psum = 0.f;
+#pragma unroll
+        for (int b = 0; b < 2; b++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], c, -mc));
+                s[b][r] = p;
+                psum += p;
+            }
+        l_run = l_run * corr + psum;
+#pragma unroll
+        for (int db = 0; db < D / 32; db++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) o_acc[db][r] *= corr;
+
+        // O^T += V^T P^T, 16 keys per MFMA
+#pragma unroll
+        for (int kk = 0; kk < 4; kk++) {
+            const int b = kk >> 1, r0 = 8 * (kk & 1);
+            bf16x8 pb = cvt8(s[b][r0 + 0], s[b][r0 + 1], s[b][r0 + 2], s[b][r0 + 3],
+                             s[b][r0 + 4], s[b][r0 + 5], s[b][r0 + 6], s[b][r0 + 7]);
+#pragma unroll
+            for (int db = 0; db < D / 32; db++) {
+                // rows 16*kk + 4*h + (0..3) and +8; the +8 flips bit 1 of swizzle_v's low field
+                const int row_off = 16 * kk * S::kRowBytes;
+                const int x0 = (4 * db) << 4;
+                const int x1 = ((4 * db) ^ 2) << 4;
+                bf16x4 v0 = lds_read_tr16(vs, (v_lane ^ x0) + row_off);
+                bf16x4 v1 = lds_read_tr16(vs, (v_lane ^ x1) + row_off + 8 * S::kRowBytes);
+                o_acc[db] = mfma32(concat(v0, v1), pb, o_acc[db]);
+            }
+        }
+    };
+
+    const int n_tiles = CAUSAL ? (qt * S::kTileQ + S::kTileQ) / S::kTileKV : N / S::kTileKV;   // even
+
+    issue_tile(0, 0);
+    wait_vmcnt<0>();
+    __syncthreads();
+    for (int t = 0; t < n_tiles; t += 2) {
+        issue_tile(1, t + 1);
+        compute_tile(0, t);
+        wait_vmcnt<0>();
+        __syncthreads();
+        if (t + 2 < n_tiles) issue_tile(0, t + 2);
+        compute_tile(1, t + 1);
+        wait_vmcnt<0>();
+        __syncthreads();
+    }
+
+    // ---- epilogue
+    const float l_tot = half_sum(l_run);
+    const float inv = 1.0f / l_tot;
+    bf16* Oh = O + head + (size_t)my_q * D;
+#pragma unroll
+    for (int db = 0; db < D / 32; db++)
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+            bf16x2 a = cvt2(o_acc[db][4 * g + 0] * inv, o_acc[db][4 * g + 1] * inv);
+            bf16x2 b = cvt2(o_acc[db][4 * g + 2] * inv, o_acc[db][4 * g + 3] * inv);
+            *(bf16x4*)(Oh + 32 * db + 8 * g + 4 * h) = __builtin_shufflevector(a, b, 0, 1, 2, 3);
+        }
+    if (h == 0) LSE[(size_t)bh * N + my_q] = m_run * scale + __builtin_logf(l_tot);
+}
+
+template <int D, bool CAUSAL>
+static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, void* o, float* lse,
+                               int B, int H, int N, float scale, hipStream_t stream)
+{
+    using S = FwdShape<D>;
+    auto kern = attn_fwd_kernel<D, CAUSAL>;
+    static bool configured = false;   // attribute is per function; idempotent, so a benign race at worst repeats it
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::kLdsBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int num_q_tiles = N / S::kTileQ;
+    const int total = B * H * num_q_tiles;
+    hipLaunchKernelGGL(kern, dim3(total), dim3(S::kThreads), S::kLdsBytes, stream,
+                       (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, lse,
+                       N, num_q_tiles, total, scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                           int B, int H, int N, int D, int causal, float scale, hipStream_t stream)
+{
+    if (D == 128) return causal ? launch_fwd_t<128, true>(q, k, v, o, lse, B, H, N, scale, stream)
+                                : launch_fwd_t<128, false>(q, k, v, o, lse, B, H, N, scale, stream);
+    return causal ? launch_fwd_t<64, true>(q, k, v, o, lse, B, H, N, scale, stream)
+                  : launch_fwd_t<64, false>(q, k, v, o, lse, B, H, N, scale, stream);
+}
+
+}  // namespace tk

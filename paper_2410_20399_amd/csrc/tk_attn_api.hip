@@ -1,0 +1,106 @@
+// C ABI of the attention library: host-side validation and dispatch only.
+#include "../../include/tk_attn.h"
+#include "tk_launch.h"
+
+#include <math.h>
+#include <stdint.h>
+
+namespace {
+
+constexpr int kGranuleN = 128;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(int B, int H, int N, int D)
+{
+    if (D != 64 && D != 128) return TK_ERR_BAD_DIM;
+    if (B < 1 || H < 1 || N < kGranuleN || N % kGranuleN != 0) return TK_ERR_BAD_DIM;
+    const long long tiles = (long long)B * H * (N / kGranuleN);
+    if (tiles > 0x7fffffffLL) return TK_ERR_BAD_DIM;
+    return TK_OK;
+}
+
+int check_scale(float scale)
+{
+    return (isfinite(scale) && scale > 0.0f) ? TK_OK : TK_ERR_BAD_SCALE;
+}
+
+size_t delta_bytes(int B, int H, int N)
+{
+    size_t b = (size_t)B * H * N * sizeof(float);
+    return (b + 255) & ~(size_t)255;   // keep the dQ accumulator that follows 256-byte aligned
+}
+
+}  // namespace
+
+extern "C" {
+
+int tk_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                int B, int H, int N, int D, int causal, float scale, void* stream)
+{
+    if (!q || !k || !v || !o || !lse) return TK_ERR_NULL_PTR;
+    if (int rc = check_shape(B, H, N, D)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return TK_ERR_MISALIGNED;
+    if (int rc = check_scale(scale)) return rc;
+    hipError_t e = tk::launch_attn_fwd(q, k, v, o, lse, B, H, N, D, causal != 0, scale, (hipStream_t)stream);
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
+size_t tk_attn_bwd_workspace_bytes(int B, int H, int N, int D)
+{
+    if (check_shape(B, H, N, D) != TK_OK) return 0;
+    return delta_bytes(B, H, N) + (size_t)B * H * N * D * sizeof(float);
+}
+
+int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta, int B, int H, int N, int D, void* stream)
+{
+    if (!o || !d_o || !delta) return TK_ERR_NULL_PTR;
+    if (int rc = check_shape(B, H, N, D)) return rc;
+    if (!aligned16(o) || !aligned16(d_o) || !aligned16(delta)) return TK_ERR_MISALIGNED;
+    hipError_t e = tk::launch_attn_bwd_delta(o, d_o, delta, nullptr, B, H, N, D, (hipStream_t)stream);
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
+int tk_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse,
+                void* dq, void* dk, void* dv,
+                int B, int H, int N, int D, int causal, float scale,
+                void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return TK_ERR_NULL_PTR;
+    if (int rc = check_shape(B, H, N, D)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(lse) ||
+        !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
+        return TK_ERR_MISALIGNED;
+    if (int rc = check_scale(scale)) return rc;
+    if (workspace_bytes < tk_attn_bwd_workspace_bytes(B, H, N, D)) return TK_ERR_WORKSPACE_TOO_SMALL;
+
+    hipStream_t s = (hipStream_t)stream;
+    float* delta = (float*)workspace;
+    float* dq_acc = (float*)((char*)workspace + delta_bytes(B, H, N));
+    // 1. Delta = rowsum(dO * O); the same sweep clears the fp32 dQ accumulator
+    if (tk::launch_attn_bwd_delta(o, d_o, delta, dq_acc, B, H, N, D, s) != hipSuccess) return TK_ERR_LAUNCH;
+    // 2. dK, dV per key tile; dQ partial products accumulated with fp32 atomics
+    if (tk::launch_attn_bwd_main(q, k, v, d_o, lse, delta, dq_acc, dk, dv, B, H, N, D, causal != 0, scale, s) != hipSuccess)
+        return TK_ERR_LAUNCH;
+    // 3. dQ = bf16(scale * accumulator)
+    if (tk::launch_attn_bwd_dq_convert(dq_acc, dq, (size_t)B * H * N * D, scale, s) != hipSuccess) return TK_ERR_LAUNCH;
+    return TK_OK;
+}
+
+const char* tk_status_string(int status)
+{
+    switch (status) {
+        case TK_OK: return "ok";
+        case TK_ERR_NULL_PTR: return "null pointer";
+        case TK_ERR_BAD_DIM: return "unsupported shape (D must be 64 or 128, N a positive multiple of 128, B,H >= 1)";
+        case TK_ERR_MISALIGNED: return "pointer not 16-byte aligned";
+        case TK_ERR_BAD_SCALE: return "scale must be finite and > 0";
+        case TK_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case TK_ERR_LAUNCH: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int tk_attn_version(void) { return 100; }
+
+}  // extern "C"
