@@ -1,0 +1,129 @@
+"""Host-side checks of the C ABI (no GPU needed): the library loads, exports every symbol the
+header declares, and rejects bad arguments before making any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tk_attn.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2410_20399_amd import attn, build
+    if build.stale():
+        build.build()
+    return attn.load_library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tk_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_expected_entry_points():
+    names = declared_functions()
+    for must in ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
+                 "tk_status_string", "tk_attn_version"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    from paper_2410_20399_amd import attn
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} declared in tk_attn.h but not exported"
+    assert sorted(attn.EXPORTS) == declared_functions()
+
+
+def test_version_and_status_strings(lib):
+    from paper_2410_20399_amd import attn
+    assert attn.version() >= 100
+    seen = set()
+    for code in range(0, -7, -1):
+        s = attn.status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 7
+    assert attn.status_string(-99) == "unknown status"
+
+
+P = ctypes.c_void_p(0x10000)        # never dereferenced: validation fails first
+ODD = ctypes.c_void_p(0x10008)      # 8-byte aligned only
+
+
+def fwd(lib, q=P, k=P, v=P, o=P, lse=P, B=1, H=1, N=128, D=64, causal=0, scale=0.125):
+    return lib.tk_attn_fwd(q, k, v, o, lse, B, H, N, D, causal, ctypes.c_float(scale), None)
+
+
+def bwd(lib, ptrs=None, B=1, H=1, N=128, D=64, causal=0, scale=0.125, ws=P, ws_bytes=1 << 40):
+    ptrs = ptrs or [P] * 9
+    return lib.tk_attn_bwd(*ptrs, B, H, N, D, causal, ctypes.c_float(scale), ws, ctypes.c_size_t(ws_bytes), None)
+
+
+def test_forward_rejects_bad_arguments(lib):
+    from paper_2410_20399_amd import attn as a
+    for name in ("q", "k", "v", "o", "lse"):
+        assert fwd(lib, **{name: None}) == a.TK_ERR_NULL_PTR
+    for bad in (dict(D=32), dict(D=96), dict(D=256), dict(N=0), dict(N=-128), dict(N=64), dict(N=200),
+                dict(B=0), dict(H=0), dict(B=-1), dict(B=1 << 20, H=1 << 12, N=128)):
+        assert fwd(lib, **bad) == a.TK_ERR_BAD_DIM, bad
+    for name in ("q", "k", "v", "o", "lse"):
+        assert fwd(lib, **{name: ODD}) == a.TK_ERR_MISALIGNED
+    for s in (0.0, -0.125, float("inf"), float("nan")):
+        assert fwd(lib, scale=s) == a.TK_ERR_BAD_SCALE
+
+
+def test_backward_rejects_bad_arguments(lib):
+    from paper_2410_20399_amd import attn as a
+    for i in range(9):
+        ptrs = [P] * 9
+        ptrs[i] = None
+        assert bwd(lib, ptrs) == a.TK_ERR_NULL_PTR
+        ptrs[i] = ODD
+        assert bwd(lib, ptrs) == a.TK_ERR_MISALIGNED
+    assert bwd(lib, ws=None) == a.TK_ERR_NULL_PTR
+    assert bwd(lib, ws=ODD) == a.TK_ERR_MISALIGNED
+    assert bwd(lib, D=100) == a.TK_ERR_BAD_DIM
+    assert bwd(lib, N=129) == a.TK_ERR_BAD_DIM
+    assert bwd(lib, scale=-1.0) == a.TK_ERR_BAD_SCALE
+    need = lib.tk_attn_bwd_workspace_bytes(1, 1, 128, 64)
+    assert bwd(lib, ws_bytes=need - 1) == a.TK_ERR_WORKSPACE_TOO_SMALL
+    assert bwd(lib, ws_bytes=0) == a.TK_ERR_WORKSPACE_TOO_SMALL
+
+
+def test_workspace_size(lib):
+    # fp32 Delta [B,H,N] (padded to 256 B) + fp32 dQ accumulator [B,H,N,D]
+    assert lib.tk_attn_bwd_workspace_bytes(1, 1, 128, 64) == 128 * 4 + 128 * 64 * 4
+    assert lib.tk_attn_bwd_workspace_bytes(16, 16, 4096, 128) == 16 * 16 * 4096 * 4 * (1 + 128)
+    assert lib.tk_attn_bwd_workspace_bytes(1, 1, 100, 64) == 0
+    assert lib.tk_attn_bwd_workspace_bytes(1, 1, 128, 80) == 0
+
+
+def test_delta_entry_rejects_bad_arguments(lib):
+    from paper_2410_20399_amd import attn as a
+    assert lib.tk_attn_bwd_delta(None, P, P, 1, 1, 128, 64, None) == a.TK_ERR_NULL_PTR
+    assert lib.tk_attn_bwd_delta(P, P, ODD, 1, 1, 128, 64, None) == a.TK_ERR_MISALIGNED
+    assert lib.tk_attn_bwd_delta(P, P, P, 1, 1, 128, 48, None) == a.TK_ERR_BAD_DIM
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    from paper_2410_20399_amd import attn
+    saved = attn._lib
+    attn._lib = None
+    try:
+        with pytest.raises(FileNotFoundError):
+            attn.load_library(str(tmp_path / "libtk_attn.so"))
+    finally:
+        attn._lib = saved
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2410_20399_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower() or f == "workloads.py", f
