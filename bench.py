@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused attention hot path on one MI355X.
+
+One step = one forward (tk_attn_fwd) plus one backward (tk_attn_bwd) over one synthetic batch
+of the target shape B=16, H=16, N=4096, D=128, causal, bf16 - the shape the performance
+target is quoted on.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is the whole step's TFLOP/s under the usual convention
+(forward 4*B*H*N^2*D, backward 2.5x that, halved when causal).  `roofline` describes the
+dominant kernel (the backward dK/dV/dQ kernel) against the dense bf16 MFMA peak, timed
+with HIP events on the launch stream; `cpu_baseline` is the fp64 oracle timed on the
+host cores of the same box on a few heads of the same workload.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (published: 2.5 PFLOP/s)
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=6, help="index into workloads.WORKLOADS (default: the target shape)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; heads are independent, so N GPUs would each run "
+              "this same benchmark on B*H/N heads (no multi-GPU figure is produced).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2410_20399_amd import attn, workloads
+
+    attn.load_library()                       # raises if the HIP library is missing: no fallback
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    w = workloads.WORKLOADS[args.workload]
+    q, k, v, d_o = workloads.make_inputs(w, need_do=True)
+    qd, kd, vd, dod = (t.to(dev) for t in (q, k, v, d_o))
+    B, H, N, D = w.B, w.H, w.N, w.D
+    o = torch.empty_like(qd)
+    lse = torch.empty((B, H, N), dtype=torch.float32, device=dev)
+    dq, dk, dv = torch.empty_like(qd), torch.empty_like(qd), torch.empty_like(qd)
+    ws = attn.alloc_bwd_workspace(B, H, N, D, dev)
+    ws_bytes = ws.numel()
+    stream = torch.cuda.current_stream()
+
+    def check(rc, what):
+        if rc != attn.TK_OK:
+            raise attn.TkAttnError(rc, what)
+
+    def step():
+        check(attn.tk_attn_fwd(qd, kd, vd, o, lse, B, H, N, D, w.causal, w.scale, stream), "tk_attn_fwd")
+        if w.backward:
+            check(attn.tk_attn_bwd(qd, kd, vd, o, dod, lse, dq, dk, dv, B, H, N, D, w.causal, w.scale,
+                                   ws, ws_bytes, stream), "tk_attn_bwd")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    flops_fwd = w.fwd_flops()
+    flops_bwd = w.bwd_flops() if w.backward else 0.0
+    value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-kernel durations: the same kernels through the stage entry points, HIP events on the launch stream
+    delta_off = (B * H * N * 4 + 255) // 256 * 256
+    delta = ws[:B * H * N * 4].view(torch.float32)
+    dq_acc = ws[delta_off:delta_off + B * H * N * D * 4].view(torch.float32)
+
+    stages = [("attn_fwd_kernel", lambda: check(attn.tk_attn_fwd(qd, kd, vd, o, lse, B, H, N, D, w.causal, w.scale, stream), "fwd"))]
+    if w.backward:
+        stages += [
+            ("attn_bwd_delta_kernel", lambda: check(attn.tk_attn_bwd_delta(o, dod, delta, dq_acc, B, H, N, D, stream), "delta")),
+            ("attn_bwd_main_kernel", lambda: check(attn.tk_attn_bwd_main(qd, kd, vd, dod, lse, delta, dq_acc, dk, dv, B, H, N, D, w.causal, w.scale, stream), "main")),
+            ("attn_bwd_dq_convert_kernel", lambda: check(attn.tk_attn_bwd_dq_convert(dq_acc, dq, B, H, N, D, w.scale, stream), "convert")),
+        ]
+    kernel_ms = {name: 0.0 for name, _ in stages}
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)] for _ in range(args.steps)]
+    for s in range(args.steps):
+        evs[s][0].record(stream)
+        for i, (_, fn) in enumerate(stages):
+            fn()
+            evs[s][i + 1].record(stream)
+    torch.cuda.synchronize()
+    for s in range(args.steps):
+        for i, (name, _) in enumerate(stages):
+            kernel_ms[name] += evs[s][i].elapsed_time(evs[s][i + 1]) / args.steps
+
+    fwd_tflops = flops_fwd / (kernel_ms["attn_fwd_kernel"] * 1e-3) / 1e12
+    out = {
+        "metric": "attention fwd+bwd TFLOPS (bf16, causal, N=4096, D=128)" if args.workload == 6 else f"attention TFLOPS ({w.name})",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "B": B, "H": H, "N": N, "D": D, "causal": w.causal,
+                   "pass": "fwd+bwd" if w.backward else "fwd",
+                   "flop_convention": "fwd 4*B*H*N^2*D, bwd 2.5x fwd, halved when causal"},
+        "frac_of_mfma_peak": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
+        "fwd": {"ms": round(kernel_ms["attn_fwd_kernel"], 4), "tflops": round(fwd_tflops, 2),
+                "frac_of_mfma_peak": round(fwd_tflops / MFMA_BF16_PEAK_TFLOPS, 4)},
+        "kernel_ms": {k_: round(v_, 4) for k_, v_ in kernel_ms.items()},
+    }
+    if w.backward:
+        bwd_ms = kernel_ms["attn_bwd_delta_kernel"] + kernel_ms["attn_bwd_main_kernel"] + kernel_ms["attn_bwd_dq_convert_kernel"]
+        bwd_tflops = flops_bwd / (bwd_ms * 1e-3) / 1e12
+        main_tflops = flops_bwd / (kernel_ms["attn_bwd_main_kernel"] * 1e-3) / 1e12
+        out["bwd"] = {"ms": round(bwd_ms, 4), "tflops": round(bwd_tflops, 2),
+                      "frac_of_mfma_peak": round(bwd_tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
+        delta_bytes = 2 * B * H * N * D * 2 + B * H * N * 4       # read O, dO; write Delta (the dQ zero-fill rides along)
+        out["delta_stage"] = {"ms": round(kernel_ms["attn_bwd_delta_kernel"], 4),
+                              "algorithmic_GBps": round(delta_bytes / (kernel_ms["attn_bwd_delta_kernel"] * 1e-3) / 1e9, 1),
+                              "with_dq_zero_fill_GBps": round((delta_bytes + B * H * N * D * 4) / (kernel_ms["attn_bwd_delta_kernel"] * 1e-3) / 1e9, 1),
+                              "hbm_peak_GBps": HBM_PEAK_GBS}
+        out["roofline"] = {"kernel": "attn_bwd_main_kernel", "bound": "mfma", "achieved": round(main_tflops, 2),
+                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                           "frac": round(main_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+    else:
+        out["roofline"] = {"kernel": "attn_fwd_kernel", "bound": "mfma", "achieved": round(fwd_tflops, 2),
+                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                           "frac": round(fwd_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
+    if not args.no_cpu_baseline:
+        from oracle import attn_oracle as orc
+        heads, spent, cpu_flops = [], 0.0, 0.0
+        per_head = (flops_fwd + flops_bwd) / (B * H)
+        n_max = min(64, B * H)
+        for idx in range(n_max):
+            b, h = divmod(idx * (B * H // n_max), H)
+            a = [t[b, h].double().numpy() for t in ((q, k, v, d_o) if w.backward else (q, k, v))]
+            c0 = time.perf_counter()
+            orc.attn_fwd(a[0], a[1], a[2], w.causal, w.scale)
+            if w.backward:
+                orc.attn_bwd(a[0], a[1], a[2], a[3], w.causal, w.scale)
+            spent += time.perf_counter() - c0
+            cpu_flops += per_head
+            heads.append([b, h])
+            if spent >= args.cpu_seconds:
+                break
+        out["cpu_baseline"] = {"value": round(cpu_flops / spent / 1e12, 6), "unit": "TFLOP/s",
+                               "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"fp64 oracle fwd{'+bwd' if w.backward else ''} on {len(heads)} of {B * H} heads "
+                                         f"(b,h)={heads[0]}..{heads[-1]} in steps of {B * H // n_max} flat heads, {spent:.1f} s, same FLOP convention"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -96,12 +96,30 @@ int tk_attn_bwd(const void* q, const void* k, const void* v,
 size_t tk_attn_bwd_workspace_bytes(int B, int H, int N, int D);
 
 /*
- * The first stage of the backward pass on its own: Delta_i = sum_d dO_id O_id.
- * o, d_o : in, bf16 [B,H,N,D];  delta : out, fp32 [B,H,N].  (D, N rules as above.)
- * Exposed so that its memory throughput can be measured separately.
+ * The three stages of tk_attn_bwd as separate calls, so that each kernel's throughput can be
+ * measured on its own (tk_attn_bwd runs exactly these, in this order, on one stream).
+ * Same pointer, shape and error conventions as above.
+ *
+ * Stage 1: Delta_i = sum_d dO_id O_id.
+ *   o, d_o : in, bf16 [B,H,N,D];  delta : out, fp32 [B,H,N]
+ *   dq_acc : NULL, or fp32 [B,H,N,D] that the same sweep fills with zeros
  */
-int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta,
+int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta, float* dq_acc,
                       int B, int H, int N, int D, void* stream);
+
+/*
+ * Stage 2: dK, dV (bf16 out) and the partial dQ products, which are ADDED (fp32 atomics,
+ * unscaled) into dq_acc; the caller must have zeroed dq_acc (stage 1 can).
+ *   lse, delta : in, fp32 [B,H,N];  dq_acc : in/out, fp32 [B,H,N,D]
+ */
+int tk_attn_bwd_main(const void* q, const void* k, const void* v, const void* d_o,
+                     const float* lse, const float* delta, float* dq_acc,
+                     void* dk, void* dv,
+                     int B, int H, int N, int D, int causal, float scale, void* stream);
+
+/* Stage 3: dq = bf16(scale * dq_acc).  dq_acc : in, fp32 [B,H,N,D];  dq : out, bf16 [B,H,N,D] */
+int tk_attn_bwd_dq_convert(const float* dq_acc, void* dq,
+                           int B, int H, int N, int D, float scale, void* stream);
 
 /* Human-readable name of a status code (static storage; never NULL). */
 const char* tk_status_string(int status);

@@ -52,12 +52,38 @@ size_t tk_attn_bwd_workspace_bytes(int B, int H, int N, int D)
     return delta_bytes(B, H, N) + (size_t)B * H * N * D * sizeof(float);
 }
 
-int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta, int B, int H, int N, int D, void* stream)
+int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta, float* dq_acc,
+                      int B, int H, int N, int D, void* stream)
 {
     if (!o || !d_o || !delta) return TK_ERR_NULL_PTR;
     if (int rc = check_shape(B, H, N, D)) return rc;
-    if (!aligned16(o) || !aligned16(d_o) || !aligned16(delta)) return TK_ERR_MISALIGNED;
-    hipError_t e = tk::launch_attn_bwd_delta(o, d_o, delta, nullptr, B, H, N, D, (hipStream_t)stream);
+    if (!aligned16(o) || !aligned16(d_o) || !aligned16(delta) || !aligned16(dq_acc)) return TK_ERR_MISALIGNED;
+    hipError_t e = tk::launch_attn_bwd_delta(o, d_o, delta, dq_acc, B, H, N, D, (hipStream_t)stream);
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
+int tk_attn_bwd_main(const void* q, const void* k, const void* v, const void* d_o,
+                     const float* lse, const float* delta, float* dq_acc, void* dk, void* dv,
+                     int B, int H, int N, int D, int causal, float scale, void* stream)
+{
+    if (!q || !k || !v || !d_o || !lse || !delta || !dq_acc || !dk || !dv) return TK_ERR_NULL_PTR;
+    if (int rc = check_shape(B, H, N, D)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(lse) ||
+        !aligned16(delta) || !aligned16(dq_acc) || !aligned16(dk) || !aligned16(dv))
+        return TK_ERR_MISALIGNED;
+    if (int rc = check_scale(scale)) return rc;
+    hipError_t e = tk::launch_attn_bwd_main(q, k, v, d_o, lse, delta, dq_acc, dk, dv, B, H, N, D, causal != 0, scale,
+                                            (hipStream_t)stream);
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
+int tk_attn_bwd_dq_convert(const float* dq_acc, void* dq, int B, int H, int N, int D, float scale, void* stream)
+{
+    if (!dq_acc || !dq) return TK_ERR_NULL_PTR;
+    if (int rc = check_shape(B, H, N, D)) return rc;
+    if (!aligned16(dq_acc) || !aligned16(dq)) return TK_ERR_MISALIGNED;
+    if (int rc = check_scale(scale)) return rc;
+    hipError_t e = tk::launch_attn_bwd_dq_convert(dq_acc, dq, (size_t)B * H * N * D, scale, (hipStream_t)stream);
     return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
 }
 
