@@ -48,7 +48,11 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
                      int N, int num_q_tiles, int total_wg, float scale)
 {
     using S = FwdShape<D>;
-    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    // One array per ring stage: distinct LDS objects let the compiler see that reads of the stage
+    // being consumed cannot alias the direct-to-LDS loads in flight into the other stage (otherwise
+    // it drains every outstanding load before the first LDS read that follows them).
+    __shared__ __attribute__((aligned(1024))) char smem0[S::kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char smem1[S::kStageBytes];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -90,13 +94,14 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
     auto issue_tile = [&](int stage, int tile) {
         const bf16* kt = Kh + (size_t)tile * S::kTileKV * D;
         const bf16* vt = Vh + (size_t)tile * S::kTileKV * D;
-        char* base = smem + stage * S::kStageBytes + wave * 1024;
+        char* base = (stage ? smem1 : smem0) + wave * 1024;
 #pragma unroll
         for (int it = 0; it < S::kLoadsPerTile; it++)
             load_global_to_lds16(kt + k_src[it], base + it * (S::kThreads * 16));
 #pragma unroll
         for (int it = 0; it < S::kLoadsPerTile; it++)
             load_global_to_lds16(vt + v_src[it], base + S::kTileBytes + it * (S::kThreads * 16));
+        __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of the math it overlaps with
     };
 
     // ---- per-lane LDS read offsets (the XOR with a compile-time chunk index is applied at use)
@@ -120,7 +125,7 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
     auto compute_tile = [&](int stage, int tile) {
         const int j0 = tile * S::kTileKV;
         if (CAUSAL && j0 > q0 + 31) return;          // every key of the tile is masked for this wave
-        const char* ks = smem + stage * S::kStageBytes;
+        const char* ks = stage ? smem1 : smem0;
         const char* vs = ks + S::kTileBytes;
 
         // S^T[key][query] for two 32-key blocks
@@ -151,10 +156,24 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
 #pragma unroll
         for (int r = 0; r < 16; r++) mx = __builtin_fmaxf(mx, s[1][r]);
         mx = half_max(mx);
-        const float m_new = __builtin_fmaxf(m_run, mx);
-        const float mc = m_new * c;
-        const float corr = __builtin_amdgcn_exp2f(m_run * c - mc);
-        m_run = m_new;
+        // The running max is only raised when some row of the wave outgrows it by more than
+        // kMaxSlack in the base-2 exponent: with a stale max every exponent stays <= kMaxSlack,
+        // so P <= 2^kMaxSlack is still exactly representable work for fp32/bf16, and O and l
+        // carry the same factor, which the final division removes.  Saves the O rescale on
+        // almost every tile.
+        constexpr float kMaxSlack = 8.0f;
+        const bool raise = (mx - m_run) * c > kMaxSlack;          // true on the first tile (m_run = -inf)
+        if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+            const float m_new = __builtin_fmaxf(m_run, mx);
+            const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c);
+            m_run = m_new;
+            l_run *= corr;
+#pragma unroll
+            for (int db = 0; db < D / 32; db++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) o_acc[db][r] *= corr;
+        }
+        const float mc = m_run * c;
         // P = 2^(S*c - m*c), partial row sums
         float psum = 0.f;
 #pragma unroll
@@ -165,11 +184,7 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
                 s[b][r] = p;
                 psum += p;
             }
-        l_run = l_run * corr + psum;
-#pragma unroll
-        for (int db = 0; db < D / 32; db++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) o_acc[db][r] *= corr;
+        l_run += psum;
 
         // O^T += V^T P^T, 16 keys per MFMA
 #pragma unroll
@@ -227,15 +242,9 @@ static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, void
 {
     using S = FwdShape<D>;
     auto kern = attn_fwd_kernel<D, CAUSAL>;
-    static bool configured = false;   // attribute is per function; idempotent, so a benign race at worst repeats it
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::kLdsBytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
     const int num_q_tiles = N / S::kTileQ;
     const int total = B * H * num_q_tiles;
-    hipLaunchKernelGGL(kern, dim3(total), dim3(S::kThreads), S::kLdsBytes, stream,
+    hipLaunchKernelGGL(kern, dim3(total), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, lse,
                        N, num_q_tiles, total, scale);
     return hipGetLastError();
