@@ -33,6 +33,9 @@ def main():
     ap.add_argument("--workload", type=int, default=6, help="index into workloads.WORKLOADS (default: the target shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy a few times, so that a counter run of this same "
+                         "command can scale FETCH_SIZE / WRITE_SIZE by what they read for a known transfer")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; heads are independent, so N GPUs would each run "
@@ -83,16 +86,14 @@ def main():
     value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
 
     # ---- per-kernel durations: the same kernels through the stage entry points, HIP events on the launch stream
-    delta_off = (B * H * N * 4 + 255) // 256 * 256
     delta = ws[:B * H * N * 4].view(torch.float32)
-    dq_acc = ws[delta_off:delta_off + B * H * N * D * 4].view(torch.float32)
 
     stages = [("attn_fwd_kernel", lambda: check(attn.tk_attn_fwd(qd, kd, vd, o, lse, B, H, N, D, w.causal, w.scale, stream), "fwd"))]
     if w.backward:
         stages += [
-            ("attn_bwd_delta_kernel", lambda: check(attn.tk_attn_bwd_delta(o, dod, delta, dq_acc, B, H, N, D, stream), "delta")),
-            ("attn_bwd_main_kernel", lambda: check(attn.tk_attn_bwd_main(qd, kd, vd, dod, lse, delta, dq_acc, dk, dv, B, H, N, D, w.causal, w.scale, stream), "main")),
-            ("attn_bwd_dq_convert_kernel", lambda: check(attn.tk_attn_bwd_dq_convert(dq_acc, dq, B, H, N, D, w.scale, stream), "convert")),
+            ("attn_bwd_delta_kernel", lambda: check(attn.tk_attn_bwd_delta(o, dod, delta, B, H, N, D, stream), "delta")),
+            ("attn_bwd_dkdv_kernel", lambda: check(attn.tk_attn_bwd_dkdv(qd, kd, vd, dod, lse, delta, dk, dv, B, H, N, D, w.causal, w.scale, stream), "dkdv")),
+            ("attn_bwd_dq_kernel", lambda: check(attn.tk_attn_bwd_dq(qd, kd, vd, dod, lse, delta, dq, B, H, N, D, w.causal, w.scale, stream), "dq")),
         ]
     kernel_ms = {name: 0.0 for name, _ in stages}
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)] for _ in range(args.steps)]
@@ -121,23 +122,39 @@ def main():
         "kernel_ms": {k_: round(v_, 4) for k_, v_ in kernel_ms.items()},
     }
     if w.backward:
-        bwd_ms = kernel_ms["attn_bwd_delta_kernel"] + kernel_ms["attn_bwd_main_kernel"] + kernel_ms["attn_bwd_dq_convert_kernel"]
+        bwd_ms = kernel_ms["attn_bwd_delta_kernel"] + kernel_ms["attn_bwd_dkdv_kernel"] + kernel_ms["attn_bwd_dq_kernel"]
         bwd_tflops = flops_bwd / (bwd_ms * 1e-3) / 1e12
-        main_tflops = flops_bwd / (kernel_ms["attn_bwd_main_kernel"] * 1e-3) / 1e12
+        # the dK/dV kernel executes four of the backward's five products
+        # (S, dP, dV, dK: 8*D flops per kept query-key pair); the dQ kernel three (S, dP, dQ: 6*D)
+        dkdv_flops = flops_bwd * 4.0 / 5.0
+        main_tflops = dkdv_flops / (kernel_ms["attn_bwd_dkdv_kernel"] * 1e-3) / 1e12
+        dq_tflops = flops_bwd * 3.0 / 5.0 / (kernel_ms["attn_bwd_dq_kernel"] * 1e-3) / 1e12
         out["bwd"] = {"ms": round(bwd_ms, 4), "tflops": round(bwd_tflops, 2),
                       "frac_of_mfma_peak": round(bwd_tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
-        delta_bytes = 2 * B * H * N * D * 2 + B * H * N * 4       # read O, dO; write Delta (the dQ zero-fill rides along)
+        delta_bytes = 2 * B * H * N * D * 2 + B * H * N * 4       # read O, dO; write Delta
         out["delta_stage"] = {"ms": round(kernel_ms["attn_bwd_delta_kernel"], 4),
                               "algorithmic_GBps": round(delta_bytes / (kernel_ms["attn_bwd_delta_kernel"] * 1e-3) / 1e9, 1),
-                              "with_dq_zero_fill_GBps": round((delta_bytes + B * H * N * D * 4) / (kernel_ms["attn_bwd_delta_kernel"] * 1e-3) / 1e9, 1),
-                              "hbm_peak_GBps": HBM_PEAK_GBS}
-        out["roofline"] = {"kernel": "attn_bwd_main_kernel", "bound": "mfma", "achieved": round(main_tflops, 2),
+                              "hbm_peak_GBps": HBM_PEAK_GBS,
+                              "frac_of_hbm_peak": round(delta_bytes / (kernel_ms["attn_bwd_delta_kernel"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        out["dq_kernel"] = {"ms": round(kernel_ms["attn_bwd_dq_kernel"], 4), "executed_tflops": round(dq_tflops, 2),
+                            "frac_of_mfma_peak": round(dq_tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
+        out["roofline"] = {"kernel": "attn_bwd_dkdv_kernel", "bound": "mfma", "achieved": round(main_tflops, 2),
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                           "frac": round(main_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+                           "frac": round(main_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                           "flops_per_launch": dkdv_flops}
     else:
         out["roofline"] = {"kernel": "attn_fwd_kernel", "bound": "mfma", "achieved": round(fwd_tflops, 2),
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": round(fwd_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).fill_(1.0)   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"bytes_read": src.numel() * 2, "bytes_written": dst.numel() * 2, "launches": 3}
+        del src, dst
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
     if not args.no_cpu_baseline:

@@ -78,12 +78,10 @@ int tk_attn_fwd(const void* q, const void* k, const void* v,
  * lse             : in, fp32 [B,H,N]
  * dq, dk, dv      : out, bf16 [B,H,N,D] (fp32 accumulation)
  * workspace       : device scratch of at least tk_attn_bwd_workspace_bytes(B,H,N,D) bytes,
- *                   16-byte aligned; holds Delta (fp32 [B,H,N]) and the fp32 dQ accumulator
- *                   ([B,H,N,D]).  The library clears what it needs on the stream; contents
- *                   after the call are unspecified.  Two calls that overlap in time must
- *                   not share a workspace.
- * dQ is accumulated with fp32 atomics across key tiles, so its low-order bits
- * may differ from run to run; dK and dV are bit-reproducible.
+ *                   16-byte aligned; holds Delta (fp32 [B,H,N]).  It need not be cleared;
+ *                   contents after the call are unspecified.  Two calls that overlap in time
+ *                   must not share a workspace.
+ * No atomics are used: dQ, dK and dV are bit-reproducible from run to run.
  */
 int tk_attn_bwd(const void* q, const void* k, const void* v,
                 const void* o, const void* d_o, const float* lse,
@@ -102,24 +100,27 @@ size_t tk_attn_bwd_workspace_bytes(int B, int H, int N, int D);
  *
  * Stage 1: Delta_i = sum_d dO_id O_id.
  *   o, d_o : in, bf16 [B,H,N,D];  delta : out, fp32 [B,H,N]
- *   dq_acc : NULL, or fp32 [B,H,N,D] that the same sweep fills with zeros
  */
-int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta, float* dq_acc,
+int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta,
                       int B, int H, int N, int D, void* stream);
 
 /*
- * Stage 2: dK, dV (bf16 out) and the partial dQ products, which are ADDED (fp32 atomics,
- * unscaled) into dq_acc; the caller must have zeroed dq_acc (stage 1 can).
- *   lse, delta : in, fp32 [B,H,N];  dq_acc : in/out, fp32 [B,H,N,D]
+ * Stage 2: dK and dV (bf16 out), one workgroup per tile of 128 keys.
+ *   lse, delta : in, fp32 [B,H,N]
  */
-int tk_attn_bwd_main(const void* q, const void* k, const void* v, const void* d_o,
-                     const float* lse, const float* delta, float* dq_acc,
+int tk_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
+                     const float* lse, const float* delta,
                      void* dk, void* dv,
                      int B, int H, int N, int D, int causal, float scale, void* stream);
 
-/* Stage 3: dq = bf16(scale * dq_acc).  dq_acc : in, fp32 [B,H,N,D];  dq : out, bf16 [B,H,N,D] */
-int tk_attn_bwd_dq_convert(const float* dq_acc, void* dq,
-                           int B, int H, int N, int D, float scale, void* stream);
+/*
+ * Stage 3: dQ (bf16 out), one workgroup per tile of 128 queries; independent of stage 2.
+ *   lse, delta : in, fp32 [B,H,N]
+ */
+int tk_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
+                   const float* lse, const float* delta,
+                   void* dq,
+                   int B, int H, int N, int D, int causal, float scale, void* stream);
 
 /* Human-readable name of a status code (static storage; never NULL). */
 const char* tk_status_string(int status);

@@ -22,7 +22,7 @@ TK_ERR_WORKSPACE_TOO_SMALL = -5
 TK_ERR_LAUNCH = -6
 
 EXPORTS = ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
-           "tk_attn_bwd_main", "tk_attn_bwd_dq_convert", "tk_status_string", "tk_attn_version")
+           "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_status_string", "tk_attn_version")
 
 _lib = None
 
@@ -50,12 +50,12 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.tk_attn_bwd.restype = i
     lib.tk_attn_bwd_workspace_bytes.argtypes = [i, i, i, i]
     lib.tk_attn_bwd_workspace_bytes.restype = sz
-    lib.tk_attn_bwd_delta.argtypes = [vp, vp, fp, fp, i, i, i, i, vp]
+    lib.tk_attn_bwd_delta.argtypes = [vp, vp, fp, i, i, i, i, vp]
     lib.tk_attn_bwd_delta.restype = i
-    lib.tk_attn_bwd_main.argtypes = [vp, vp, vp, vp, fp, fp, fp, vp, vp, i, i, i, i, i, f, vp]
-    lib.tk_attn_bwd_main.restype = i
-    lib.tk_attn_bwd_dq_convert.argtypes = [fp, vp, i, i, i, i, f, vp]
-    lib.tk_attn_bwd_dq_convert.restype = i
+    lib.tk_attn_bwd_dkdv.argtypes = [vp, vp, vp, vp, fp, fp, vp, vp, i, i, i, i, i, f, vp]
+    lib.tk_attn_bwd_dkdv.restype = i
+    lib.tk_attn_bwd_dq.argtypes = [vp, vp, vp, vp, fp, fp, vp, i, i, i, i, i, f, vp]
+    lib.tk_attn_bwd_dq.restype = i
     lib.tk_status_string.argtypes = [i]
     lib.tk_status_string.restype = ctypes.c_char_p
     lib.tk_attn_version.argtypes = []
@@ -111,20 +111,19 @@ def tk_attn_bwd_workspace_bytes(B, H, N, D) -> int:
     return int(load_library().tk_attn_bwd_workspace_bytes(B, H, N, D))
 
 
-def tk_attn_bwd_delta(o, d_o, delta, dq_acc, B, H, N, D, stream=None) -> int:
-    return load_library().tk_attn_bwd_delta(_ptr(o), _ptr(d_o), _ptr(delta), _ptr(dq_acc), B, H, N, D,
-                                            _stream(stream))
+def tk_attn_bwd_delta(o, d_o, delta, B, H, N, D, stream=None) -> int:
+    return load_library().tk_attn_bwd_delta(_ptr(o), _ptr(d_o), _ptr(delta), B, H, N, D, _stream(stream))
 
 
-def tk_attn_bwd_main(q, k, v, d_o, lse, delta, dq_acc, dk, dv, B, H, N, D, causal, scale, stream=None) -> int:
-    return load_library().tk_attn_bwd_main(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(delta),
-                                           _ptr(dq_acc), _ptr(dk), _ptr(dv), B, H, N, D, int(bool(causal)),
+def tk_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, H, N, D, causal, scale, stream=None) -> int:
+    return load_library().tk_attn_bwd_dkdv(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(delta),
+                                           _ptr(dk), _ptr(dv), B, H, N, D, int(bool(causal)),
                                            float(scale), _stream(stream))
 
 
-def tk_attn_bwd_dq_convert(dq_acc, dq, B, H, N, D, scale, stream=None) -> int:
-    return load_library().tk_attn_bwd_dq_convert(_ptr(dq_acc), _ptr(dq), B, H, N, D, float(scale),
-                                                 _stream(stream))
+def tk_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, H, N, D, causal, scale, stream=None) -> int:
+    return load_library().tk_attn_bwd_dq(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(delta),
+                                         _ptr(dq), B, H, N, D, int(bool(causal)), float(scale), _stream(stream))
 
 
 # ------------------------------------------------------------------ convenience: allocate outputs, raise on error
@@ -179,7 +178,7 @@ def attn_bwd_delta(o, d_o, stream=None):
     _check_bf16("d_o", d_o, o.shape)
     B, H, N, D = o.shape
     delta = torch.empty((B, H, N), dtype=torch.float32, device=o.device)
-    rc = tk_attn_bwd_delta(o, d_o, delta, None, B, H, N, D, stream)
+    rc = tk_attn_bwd_delta(o, d_o, delta, B, H, N, D, stream)
     if rc != TK_OK:
         raise TkAttnError(rc, "tk_attn_bwd_delta")
     return delta

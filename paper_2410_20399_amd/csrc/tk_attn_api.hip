@@ -28,7 +28,7 @@ int check_scale(float scale)
 size_t delta_bytes(int B, int H, int N)
 {
     size_t b = (size_t)B * H * N * sizeof(float);
-    return (b + 255) & ~(size_t)255;   // keep the dQ accumulator that follows 256-byte aligned
+    return (b + 255) & ~(size_t)255;
 }
 
 }  // namespace
@@ -49,41 +49,45 @@ int tk_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse
 size_t tk_attn_bwd_workspace_bytes(int B, int H, int N, int D)
 {
     if (check_shape(B, H, N, D) != TK_OK) return 0;
-    return delta_bytes(B, H, N) + (size_t)B * H * N * D * sizeof(float);
+    return delta_bytes(B, H, N);
 }
 
-int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta, float* dq_acc,
-                      int B, int H, int N, int D, void* stream)
+int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta, int B, int H, int N, int D, void* stream)
 {
     if (!o || !d_o || !delta) return TK_ERR_NULL_PTR;
     if (int rc = check_shape(B, H, N, D)) return rc;
-    if (!aligned16(o) || !aligned16(d_o) || !aligned16(delta) || !aligned16(dq_acc)) return TK_ERR_MISALIGNED;
-    hipError_t e = tk::launch_attn_bwd_delta(o, d_o, delta, dq_acc, B, H, N, D, (hipStream_t)stream);
+    if (!aligned16(o) || !aligned16(d_o) || !aligned16(delta)) return TK_ERR_MISALIGNED;
+    hipError_t e = tk::launch_attn_bwd_delta(o, d_o, delta, B, H, N, D, (hipStream_t)stream);
     return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
 }
 
-int tk_attn_bwd_main(const void* q, const void* k, const void* v, const void* d_o,
-                     const float* lse, const float* delta, float* dq_acc, void* dk, void* dv,
+int tk_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
+                     const float* lse, const float* delta, void* dk, void* dv,
                      int B, int H, int N, int D, int causal, float scale, void* stream)
 {
-    if (!q || !k || !v || !d_o || !lse || !delta || !dq_acc || !dk || !dv) return TK_ERR_NULL_PTR;
+    if (!q || !k || !v || !d_o || !lse || !delta || !dk || !dv) return TK_ERR_NULL_PTR;
     if (int rc = check_shape(B, H, N, D)) return rc;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(lse) ||
-        !aligned16(delta) || !aligned16(dq_acc) || !aligned16(dk) || !aligned16(dv))
+        !aligned16(delta) || !aligned16(dk) || !aligned16(dv))
         return TK_ERR_MISALIGNED;
     if (int rc = check_scale(scale)) return rc;
-    hipError_t e = tk::launch_attn_bwd_main(q, k, v, d_o, lse, delta, dq_acc, dk, dv, B, H, N, D, causal != 0, scale,
+    hipError_t e = tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, H, N, D, causal != 0, scale,
                                             (hipStream_t)stream);
     return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
 }
 
-int tk_attn_bwd_dq_convert(const float* dq_acc, void* dq, int B, int H, int N, int D, float scale, void* stream)
+int tk_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
+                   const float* lse, const float* delta, void* dq,
+                   int B, int H, int N, int D, int causal, float scale, void* stream)
 {
-    if (!dq_acc || !dq) return TK_ERR_NULL_PTR;
+    if (!q || !k || !v || !d_o || !lse || !delta || !dq) return TK_ERR_NULL_PTR;
     if (int rc = check_shape(B, H, N, D)) return rc;
-    if (!aligned16(dq_acc) || !aligned16(dq)) return TK_ERR_MISALIGNED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(lse) ||
+        !aligned16(delta) || !aligned16(dq))
+        return TK_ERR_MISALIGNED;
     if (int rc = check_scale(scale)) return rc;
-    hipError_t e = tk::launch_attn_bwd_dq_convert(dq_acc, dq, (size_t)B * H * N * D, scale, (hipStream_t)stream);
+    hipError_t e = tk::launch_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, H, N, D, causal != 0, scale,
+                                          (hipStream_t)stream);
     return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
 }
 
@@ -102,14 +106,14 @@ int tk_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
 
     hipStream_t s = (hipStream_t)stream;
     float* delta = (float*)workspace;
-    float* dq_acc = (float*)((char*)workspace + delta_bytes(B, H, N));
-    // 1. Delta = rowsum(dO * O); the same sweep clears the fp32 dQ accumulator
-    if (tk::launch_attn_bwd_delta(o, d_o, delta, dq_acc, B, H, N, D, s) != hipSuccess) return TK_ERR_LAUNCH;
-    // 2. dK, dV per key tile; dQ partial products accumulated with fp32 atomics
-    if (tk::launch_attn_bwd_main(q, k, v, d_o, lse, delta, dq_acc, dk, dv, B, H, N, D, causal != 0, scale, s) != hipSuccess)
+    // 1. Delta = rowsum(dO * O)
+    if (tk::launch_attn_bwd_delta(o, d_o, delta, B, H, N, D, s) != hipSuccess) return TK_ERR_LAUNCH;
+    // 2. dK, dV per key tile
+    if (tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, H, N, D, causal != 0, scale, s) != hipSuccess)
         return TK_ERR_LAUNCH;
-    // 3. dQ = bf16(scale * accumulator)
-    if (tk::launch_attn_bwd_dq_convert(dq_acc, dq, (size_t)B * H * N * D, scale, s) != hipSuccess) return TK_ERR_LAUNCH;
+    // 3. dQ per query tile
+    if (tk::launch_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, H, N, D, causal != 0, scale, s) != hipSuccess)
+        return TK_ERR_LAUNCH;
     return TK_OK;
 }
 

@@ -45,6 +45,17 @@ __device__ __forceinline__ void load_global_to_lds16(const void* gptr, char* lds
     __builtin_amdgcn_global_load_lds(gptr, (TK_LDS uint32_t*)lds_wave_base, 16, 0, 0);
 }
 
+// Same load, issued through inline assembly so that the compiler does not track it: its LDS-DMA
+// bookkeeping holds only a handful of loads and otherwise drains EVERY outstanding load before the
+// next LDS read.  The caller owns the ordering: wait_vmcnt<> + barrier before anyone reads the data.
+__device__ __forceinline__ void load_global_to_lds16_untracked(const void* gptr, const char* lds_wave_base) {
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(TK_LDS const char*)lds_wave_base;
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(gptr)
+                 : "m0", "memory");   // "memory": LDS contents change behind the compiler's back
+}
+
 // 16-byte LDS read as an MFMA operand (8 consecutive-k bf16).
 __device__ __forceinline__ bf16x8 lds_read_b128(const char* smem, int byte_off) {
     return *(const bf16x8*)(smem + byte_off);

@@ -8,17 +8,18 @@ namespace tk {
 hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                            int B, int H, int N, int D, int causal, float scale, hipStream_t stream);
 
-// Delta_i = sum_d dO_id O_id; optionally also clears the fp32 dQ accumulator rows it walks over.
-hipError_t launch_attn_bwd_delta(const void* o, const void* d_o, float* delta, float* dq_acc_or_null,
+// Delta_i = sum_d dO_id O_id
+hipError_t launch_attn_bwd_delta(const void* o, const void* d_o, float* delta,
                                  int B, int H, int N, int D, hipStream_t stream);
 
-hipError_t launch_attn_bwd_main(const void* q, const void* k, const void* v, const void* d_o,
-                                const float* lse, const float* delta, float* dq_acc,
-                                void* dk, void* dv,
+// dK, dV (key-tile parallel)
+hipError_t launch_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
+                                const float* lse, const float* delta, void* dk, void* dv,
                                 int B, int H, int N, int D, int causal, float scale, hipStream_t stream);
 
-// dq = bf16(scale * dq_acc)
-hipError_t launch_attn_bwd_dq_convert(const float* dq_acc, void* dq, size_t n_elems, float scale,
-                                      hipStream_t stream);
+// dQ (query-tile parallel)
+hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
+                              const float* lse, const float* delta, void* dq,
+                              int B, int H, int N, int D, int causal, float scale, hipStream_t stream);
 
 }  // namespace tk

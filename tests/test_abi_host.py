@@ -27,7 +27,7 @@ def declared_functions():
 def test_header_declares_expected_entry_points():
     names = declared_functions()
     for must in ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
-                 "tk_attn_bwd_main", "tk_attn_bwd_dq_convert", "tk_status_string", "tk_attn_version"):
+                 "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_status_string", "tk_attn_version"):
         assert must in names
 
 
@@ -95,35 +95,34 @@ def test_backward_rejects_bad_arguments(lib):
 
 
 def test_workspace_size(lib):
-    # fp32 Delta [B,H,N] (padded to 256 B) + fp32 dQ accumulator [B,H,N,D]
-    assert lib.tk_attn_bwd_workspace_bytes(1, 1, 128, 64) == 128 * 4 + 128 * 64 * 4
-    assert lib.tk_attn_bwd_workspace_bytes(16, 16, 4096, 128) == 16 * 16 * 4096 * 4 * (1 + 128)
+    # fp32 Delta [B,H,N], padded to a multiple of 256 B
+    assert lib.tk_attn_bwd_workspace_bytes(1, 1, 128, 64) == 128 * 4
+    assert lib.tk_attn_bwd_workspace_bytes(1, 3, 128, 64) == 3 * 128 * 4
+    assert lib.tk_attn_bwd_workspace_bytes(16, 16, 4096, 128) == 16 * 16 * 4096 * 4
     assert lib.tk_attn_bwd_workspace_bytes(1, 1, 100, 64) == 0
     assert lib.tk_attn_bwd_workspace_bytes(1, 1, 128, 80) == 0
 
 
 def test_delta_entry_rejects_bad_arguments(lib):
     from paper_2410_20399_amd import attn as a
-    assert lib.tk_attn_bwd_delta(None, P, P, None, 1, 1, 128, 64, None) == a.TK_ERR_NULL_PTR
-    assert lib.tk_attn_bwd_delta(P, P, ODD, None, 1, 1, 128, 64, None) == a.TK_ERR_MISALIGNED
-    assert lib.tk_attn_bwd_delta(P, P, P, ODD, 1, 1, 128, 64, None) == a.TK_ERR_MISALIGNED
-    assert lib.tk_attn_bwd_delta(P, P, P, None, 1, 1, 128, 48, None) == a.TK_ERR_BAD_DIM
+    assert lib.tk_attn_bwd_delta(None, P, P, 1, 1, 128, 64, None) == a.TK_ERR_NULL_PTR
+    assert lib.tk_attn_bwd_delta(P, P, ODD, 1, 1, 128, 64, None) == a.TK_ERR_MISALIGNED
+    assert lib.tk_attn_bwd_delta(P, P, P, 1, 1, 128, 48, None) == a.TK_ERR_BAD_DIM
 
 
 def test_stage_entries_reject_bad_arguments(lib):
     from paper_2410_20399_amd import attn as a
     f = ctypes.c_float
-    for i in range(9):
-        ptrs = [P] * 9
-        ptrs[i] = None
-        assert lib.tk_attn_bwd_main(*ptrs, 1, 1, 128, 64, 0, f(0.125), None) == a.TK_ERR_NULL_PTR
-        ptrs[i] = ODD
-        assert lib.tk_attn_bwd_main(*ptrs, 1, 1, 128, 64, 0, f(0.125), None) == a.TK_ERR_MISALIGNED
-    assert lib.tk_attn_bwd_main(*([P] * 9), 1, 1, 128, 64, 0, f(0.0), None) == a.TK_ERR_BAD_SCALE
-    assert lib.tk_attn_bwd_main(*([P] * 9), 1, 1, 120, 64, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
-    assert lib.tk_attn_bwd_dq_convert(None, P, 1, 1, 128, 64, f(0.125), None) == a.TK_ERR_NULL_PTR
-    assert lib.tk_attn_bwd_dq_convert(P, ODD, 1, 1, 128, 64, f(0.125), None) == a.TK_ERR_MISALIGNED
-    assert lib.tk_attn_bwd_dq_convert(P, P, 1, 1, 128, 60, f(0.125), None) == a.TK_ERR_BAD_DIM
+    for fn, nptr in ((lib.tk_attn_bwd_dkdv, 8), (lib.tk_attn_bwd_dq, 7)):
+        for i in range(nptr):
+            ptrs = [P] * nptr
+            ptrs[i] = None
+            assert fn(*ptrs, 1, 1, 128, 64, 0, f(0.125), None) == a.TK_ERR_NULL_PTR
+            ptrs[i] = ODD
+            assert fn(*ptrs, 1, 1, 128, 64, 0, f(0.125), None) == a.TK_ERR_MISALIGNED
+        assert fn(*([P] * nptr), 1, 1, 128, 64, 0, f(0.0), None) == a.TK_ERR_BAD_SCALE
+        assert fn(*([P] * nptr), 1, 1, 120, 64, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
+        assert fn(*([P] * nptr), 1, 1, 128, 96, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
 
 
 def test_missing_library_fails_loudly(tmp_path):
