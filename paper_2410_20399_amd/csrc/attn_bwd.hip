@@ -26,6 +26,8 @@
 #include "tk_common.h"
 #include "tk_launch.h"
 
+#include <type_traits>
+
 namespace tk {
 
 // ------------------------------------------------------------------------------------------
@@ -68,11 +70,17 @@ struct DkdvShape {
     static constexpr int kThreads = 256;
     static constexpr int kTileKV = 128;                 // keys per workgroup (32 per wave)
     static constexpr int kTileQ = 32;                   // queries per loop iteration
+#ifndef TK_DKDV_STAGES
+#define TK_DKDV_STAGES 4
+#endif
+    static constexpr int kStages = TK_DKDV_STAGES;      // LDS ring of query blocks (a power of two), filled kStages-1 blocks ahead
+    static constexpr int kAhead = kStages - 1;
     static constexpr int kRowBytes = D * 2;
     static constexpr int kChunksPerRow = D / 8;
     static constexpr int kQTileBytes = kTileQ * kRowBytes;
-    static constexpr int kStageBytes = 2 * kQTileBytes + 256;      // Q, dO, LSE[32], Delta[32]
+    static constexpr int kStageBytes = 2 * kQTileBytes + 256;      // Q, dO, LSE[32], Delta[32]; a multiple of 256
     static constexpr int kQLoads = kTileQ * kChunksPerRow / kThreads;   // per thread, per tensor
+    static constexpr int kLoadsPerBlock = 2 * kQLoads;  // per thread (wave 0 issues one more, for the statistics)
 };
 
 // Chunk swizzle of every row-major bf16 tile in the backward kernels (rows of D elements): spreads
@@ -82,18 +90,24 @@ template <int D> __device__ __forceinline__ int swz(int row) {
     return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
 }
 
+// One wave per SIMD (the dK^T, dV^T accumulators and the K, V fragments take 192 registers at
+// D = 128), so nothing hides LDS latency but the schedule itself.  Every MFMA operand is therefore
+// read one phase ahead of its use:
+//     phase 1  S, dP MFMAs from row fragments already in registers; meanwhile the transposed
+//              fragments (dO^T, Q^T) and the statistics of THIS block are read from LDS
+//     phase 2  P, dS on the vector ALU
+//     phase 3  dV^T, dK^T MFMAs from the transposed fragments; meanwhile the row fragments of the
+//              NEXT block are read from LDS
+// and the query blocks themselves arrive by direct global->LDS loads issued three blocks ahead.
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256, (D == 128 ? 1 : 2))
+__global__ __launch_bounds__(256, 1)
 void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                           const bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
                           bf16* __restrict__ dK, bf16* __restrict__ dV,
                           int N, int num_kv_tiles, int total_wg, float scale)
 {
     using S = DkdvShape<D>;
-    // one array per stage: reads of the stage being consumed provably do not alias the
-    // direct-to-LDS loads in flight into the other one
-    __shared__ __attribute__((aligned(1024))) char stage0[S::kStageBytes];
-    __shared__ __attribute__((aligned(1024))) char stage1[S::kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char ring[S::kStages * S::kStageBytes];
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -103,20 +117,58 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     const int j16 = lane & 15;
     const int ghalf = (lane >> 4) & 1;
 
+    // Work unit of a workgroup: one key tile, or, when causal, the pair (u, last - u): tile u loops
+    // over (N - 128u)/32 query blocks, so every pair carries the same work and the launch is balanced.
+    const int units = CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles;
     const int logical = xcd_remap(blockIdx.x, total_wg);
-    const int bh = logical / num_kv_tiles;
-    const int kt = logical % num_kv_tiles;         // early key tiles have the most work when causal: first
+    const int bh = logical / units;
+    const int unit = logical % units;
+    const size_t head = (size_t)bh * N * D;
+#pragma unroll 1
+    for (int pass = 0; pass < (CAUSAL ? 2 : 1); pass++) {
+    const int kt = pass == 0 ? unit : num_kv_tiles - 1 - unit;
+    if (pass == 1 && kt == unit) break;            // odd tile count: the middle tile has no partner
     const int j0 = kt * S::kTileKV;
     const int jw0 = j0 + wave * 32;                // first key of this wave
     const int my_j = jw0 + l32;
 
-    const size_t head = (size_t)bh * N * D;
     const bf16* Qh = Q + head;
     const bf16* dOh = dO + head;
     const float* LSEh = LSE + (size_t)bh * N;
     const float* Deltah = Delta + (size_t)bh * N;
 
     const float c = scale * kLog2e;
+    const int i_begin = CAUSAL ? j0 : 0;
+    const int n_blocks = (N - i_begin) / S::kTileQ;
+
+    // ---- query-block prefetch: Q, dO rows (swizzled), LSE and Delta of 32 queries
+    int q_src[S::kQLoads];
+#pragma unroll
+    for (int it = 0; it < S::kQLoads; it++) {
+        int s = it * S::kThreads + tid;
+        int row = s / S::kChunksPerRow, pc = s % S::kChunksPerRow;
+        q_src[it] = row * D + ((pc ^ swz<D>(row)) * 8);
+    }
+    // Past the last block the last one is fetched again (into a stage nobody reads), so that every
+    // call issues the same number of loads and the vmcnt waits below can count them.
+    auto issue_block = [&](int blk) {
+        const int st = blk & (S::kStages - 1);
+        const int i0 = i_begin + (blk < n_blocks ? blk : n_blocks - 1) * S::kTileQ;
+        char* base = ring + st * S::kStageBytes;
+#pragma unroll
+        for (int it = 0; it < S::kQLoads; it++)
+            load_global_to_lds16_untracked(Qh + (size_t)i0 * D + q_src[it], base + it * (S::kThreads * 16) + wave * 1024);
+#pragma unroll
+        for (int it = 0; it < S::kQLoads; it++)
+            load_global_to_lds16_untracked(dOh + (size_t)i0 * D + q_src[it],
+                                           base + S::kQTileBytes + it * (S::kThreads * 16) + wave * 1024);
+        if (wave == 0 && lane < 16) {   // 8 lanes fetch LSE[i0..i0+31], 8 lanes Delta[i0..i0+31]
+            const float* src = (lane < 8) ? (LSEh + i0 + lane * 4) : (Deltah + i0 + (lane - 8) * 4);
+            load_global_to_lds16_untracked(src, base + 2 * S::kQTileBytes);
+        }
+    };
+#pragma unroll
+    for (int b = 0; b < S::kAhead; b++) issue_block(b);
 
     // ---- K, V fragments of this wave's 32 keys (B operands of S = Q K^T and dP = dO V^T)
     bf16x8 kf[D / 16], vf[D / 16];
@@ -125,29 +177,6 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         kf[kb] = *(const bf16x8*)(K + head + (size_t)my_j * D + kb * 16 + h * 8);
         vf[kb] = *(const bf16x8*)(V + head + (size_t)my_j * D + kb * 16 + h * 8);
     }
-
-    // ---- Q / dO / LSE / Delta block loads
-    int q_src[S::kQLoads];
-#pragma unroll
-    for (int it = 0; it < S::kQLoads; it++) {
-        int s = it * S::kThreads + tid;
-        int row = s / S::kChunksPerRow, pc = s % S::kChunksPerRow;
-        q_src[it] = row * D + ((pc ^ swz<D>(row)) * 8);
-    }
-    auto issue_block = [&](char* base, int i0) {
-#pragma unroll
-        for (int it = 0; it < S::kQLoads; it++)
-            load_global_to_lds16(Qh + (size_t)i0 * D + q_src[it], base + it * (S::kThreads * 16) + wave * 1024);
-#pragma unroll
-        for (int it = 0; it < S::kQLoads; it++)
-            load_global_to_lds16(dOh + (size_t)i0 * D + q_src[it],
-                                 base + S::kQTileBytes + it * (S::kThreads * 16) + wave * 1024);
-        if (wave == 0 && lane < 16) {   // 8 lanes fetch LSE[i0..i0+31], 8 lanes Delta[i0..i0+31]
-            const float* src = (lane < 8) ? (LSEh + i0 + lane * 4) : (Deltah + i0 + (lane - 8) * 4);
-            load_global_to_lds16(src, base + 2 * S::kQTileBytes);
-        }
-        __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of the math it overlaps with
-    };
 
     // ---- per-lane LDS offsets
     // row operand (A of S and dP): row l32, logical chunk 2*kb + h
@@ -162,71 +191,138 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
 #pragma unroll
         for (int r = 0; r < 16; r++) { dk_acc[db][r] = 0.f; dv_acc[db][r] = 0.f; }
 
-    auto compute_block = [&](const char* qs, int i0) {
+    constexpr int kSteps = D / 16;          // MFMA steps of S / dP; also 2 * (D/32) steps of dV^T / dK^T
+    bf16x8 rq[kSteps], rdo[kSteps];         // row fragments of the block about to be computed
+    // transposed fragments [ks * (D/32) + db] and bf16 P / dS of a block; two sets, because the
+    // dV^T / dK^T products of a block are issued one iteration late (see the loop)
+    struct Late { bf16x8 tq[kSteps], tdo[kSteps], pb[2], dsb[2]; };
+    Late set_a, set_b;
+    {
+        bf16x8 zero;
+#pragma unroll
+        for (int e = 0; e < 8; e++) zero[e] = (bf16)0.0f;
+#pragma unroll
+        for (int i = 0; i < kSteps; i++) { set_b.tq[i] = zero; set_b.tdo[i] = zero; }
+        set_b.pb[0] = set_b.pb[1] = set_b.dsb[0] = set_b.dsb[1] = zero;
+    }
+    f32x4 lse4[4], dl4[4];
+
+    auto read_rows = [&](const char* qs, int kb) {
+        rq[kb] = lds_read_b128(qs, row_lane ^ ((2 * kb) << 4));
+        rdo[kb] = lds_read_b128(qs + S::kQTileBytes, row_lane ^ ((2 * kb) << 4));
+    };
+    auto read_transposed = [&](Late& L, const char* qs, int idx) {
+        const int ks = idx / (D / 32), db = idx % (D / 32);
+        const int row_off = 16 * ks * S::kRowBytes;
+        const int x0 = (4 * db) << 4, x1 = ((4 * db) ^ 2) << 4;
         const char* dos = qs + S::kQTileBytes;
+        L.tdo[idx] = concat(lds_read_tr16(dos, (trq_lane ^ x0) + row_off),
+                            lds_read_tr16(dos, (trq_lane ^ x1) + row_off + 8 * S::kRowBytes));
+        L.tq[idx] = concat(lds_read_tr16(qs, (trq_lane ^ x0) + row_off),
+                           lds_read_tr16(qs, (trq_lane ^ x1) + row_off + 8 * S::kRowBytes));
+    };
+    auto late_products = [&](const Late& L, int idx) {
+        const int ks = idx / (D / 32), db = idx % (D / 32);
+        dv_acc[db] = mfma32(L.tdo[idx], L.pb[ks], dv_acc[db]);
+        dk_acc[db] = mfma32(L.tq[idx], L.dsb[ks], dk_acc[db]);
+    };
+
+    // Every global load so far (K, V fragments and blocks 0..2) completes here.  The empty asm
+    // statements pin the fragment loads above this point (the compiler would otherwise sink them to
+    // their first use inside the loop and wait for them there, draining the prefetch every
+    // iteration): inside the loop the only waits on the vector memory counter are the explicit ones,
+    // which leave the newest prefetch in flight.
+#pragma unroll
+    for (int kb = 0; kb < D / 16; kb++) asm volatile("" : "+v"(kf[kb]), "+v"(vf[kb]));
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();           // blocks 0..2 landed and visible
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kb = 0; kb < kSteps; kb++) read_rows(ring, kb);
+
+    // One query block.  cur receives this block's transposed fragments and bf16 P / dS; prev holds
+    // those of the previous block, whose dV^T / dK^T products run here, interleaved with this block's
+    // vector-ALU work (P, dS), so that the matrix pipe has work while the ALU is busy.
+    auto step = [&](int blk, Late& cur, const Late& prev) {
+        const int i0 = i_begin + blk * S::kTileQ;
+        const char* qs = ring + (blk & (S::kStages - 1)) * S::kStageBytes;
+        const char* qs_next = ring + ((blk + 1) & (S::kStages - 1)) * S::kStageBytes;
         const f32x4* stat = (const f32x4*)(qs + 2 * S::kQTileBytes);
 
+        issue_block(blk + S::kAhead);       // into the stage of block blk-1, which every wave has left
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- phase 1: S = Q K^T, dP = dO V^T; read this block's transposed fragments and statistics
         f32x16 s, dp;
 #pragma unroll
         for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
-        for (int kb = 0; kb < D / 16; kb++) {
-            bf16x8 a = lds_read_b128(qs, row_lane ^ ((2 * kb) << 4));
-            s = mfma32(a, kf[kb], s);
-            bf16x8 b = lds_read_b128(dos, row_lane ^ ((2 * kb) << 4));
-            dp = mfma32(b, vf[kb], dp);
+        for (int kb = 0; kb < kSteps; kb++) {
+            s = mfma32(rq[kb], kf[kb], s);
+            dp = mfma32(rdo[kb], vf[kb], dp);
+            read_transposed(cur, qs, kb);
+            if (kb < 4) { lse4[kb] = stat[2 * kb + h]; dl4[kb] = stat[8 + 2 * kb + h]; }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // P and dS; register r <-> query i0 + 8*(r/4) + 4h + r%4, lane <-> key my_j
-        const bool diag = CAUSAL && (i0 < jw0 + 31);
+
+        // ---- phase 2 (this block's P, dS) interleaved with phase 3 of the PREVIOUS block
+        // (dV^T += dO^T P, dK^T += Q^T dS) and with the reads of the next block's row fragments
+        // (that block landed before the barrier that ended the previous iteration).
+        // register r <-> query i0 + 8*(r/4) + 4h + r%4, lane <-> key my_j
+        // Only the first few blocks of a causal tile cross the diagonal: they push the masked scores
+        // to -inf in a branch of their own (P = 2^-inf = 0), so that the common case carries no
+        // compare / select per element.
+        if (CAUSAL && (i0 < jw0 + 31)) {
+#pragma unroll
+            for (int r = 0; r < 16; r++)
+                if (i0 + 8 * (r >> 2) + 4 * h + (r & 3) < my_j) s[r] = -INFINITY;
+        }
 #pragma unroll
         for (int g = 0; g < 4; g++) {
-            f32x4 lse4 = stat[2 * g + h];
-            f32x4 dl4 = stat[8 + 2 * g + h];
 #pragma unroll
             for (int t = 0; t < 4; t++) {
                 const int r = 4 * g + t;
-                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -lse4[t] * kLog2e));
-                if (diag && (i0 + 8 * g + 4 * h + t < my_j)) p = 0.f;
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -lse4[g][t] * kLog2e));
                 s[r] = p;
-                dp[r] = p * (dp[r] - dl4[t]);
+                dp[r] = p * (dp[r] - dl4[g][t]);
             }
         }
-        bf16x8 pb[2], dsb[2];
 #pragma unroll
         for (int ks = 0; ks < 2; ks++) {
             const int r0 = 8 * ks;
-            pb[ks] = cvt8(s[r0], s[r0 + 1], s[r0 + 2], s[r0 + 3], s[r0 + 4], s[r0 + 5], s[r0 + 6], s[r0 + 7]);
-            dsb[ks] = cvt8(dp[r0], dp[r0 + 1], dp[r0 + 2], dp[r0 + 3], dp[r0 + 4], dp[r0 + 5], dp[r0 + 6], dp[r0 + 7]);
+            cur.pb[ks] = cvt8(s[r0], s[r0 + 1], s[r0 + 2], s[r0 + 3], s[r0 + 4], s[r0 + 5], s[r0 + 6], s[r0 + 7]);
+            cur.dsb[ks] = cvt8(dp[r0], dp[r0 + 1], dp[r0 + 2], dp[r0 + 3], dp[r0 + 4], dp[r0 + 5], dp[r0 + 6], dp[r0 + 7]);
         }
-        // dV^T += dO^T P ; dK^T += Q^T dS   (16 queries per MFMA)
 #pragma unroll
-        for (int ks = 0; ks < 2; ks++) {
-            const int row_off = 16 * ks * S::kRowBytes;
-#pragma unroll
-            for (int db = 0; db < D / 32; db++) {
-                const int x0 = (4 * db) << 4, x1 = ((4 * db) ^ 2) << 4;
-                bf16x4 a0 = lds_read_tr16(dos, (trq_lane ^ x0) + row_off);
-                bf16x4 a1 = lds_read_tr16(dos, (trq_lane ^ x1) + row_off + 8 * S::kRowBytes);
-                dv_acc[db] = mfma32(concat(a0, a1), pb[ks], dv_acc[db]);
-                bf16x4 b0 = lds_read_tr16(qs, (trq_lane ^ x0) + row_off);
-                bf16x4 b1 = lds_read_tr16(qs, (trq_lane ^ x1) + row_off + 8 * S::kRowBytes);
-                dk_acc[db] = mfma32(concat(b0, b1), dsb[ks], dk_acc[db]);
-            }
+        for (int idx = 0; idx < kSteps; idx++) {
+            late_products(prev, idx);
+            read_rows(qs_next, idx);        // (after the last block: stale data, never used)
         }
-        wait_vmcnt<0>();      // next block's loads (issued before this block's math) have landed
-        __syncthreads();      // ... for every wave; and this stage may be overwritten
+        // schedule: one MFMA, then a slice of the vector work and one LDS read
+#pragma unroll
+        for (int i = 0; i < 2 * kSteps; i++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);   // VALU
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+        }
+
+        // block blk+2 (issued two iterations ago) must have landed before the next iteration reads its
+        // rows; the newer prefetches may stay in flight (wave 0 issues one more load per block)
+        if (wave == 0) wait_vmcnt<(S::kAhead - 2) * (S::kLoadsPerBlock + 1)>();
+        else wait_vmcnt<(S::kAhead - 2) * S::kLoadsPerBlock>();
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
     };
 
-    const int i_begin = CAUSAL ? j0 : 0;
-    issue_block(stage0, i_begin);
-    wait_vmcnt<0>();
-    __syncthreads();
-    for (int i0 = i_begin; i0 < N; i0 += 2 * S::kTileQ) {     // (N - i_begin) / 32 is even
-        issue_block(stage1, i0 + S::kTileQ);
-        compute_block(stage0, i0);
-        if (i0 + 2 * S::kTileQ < N) issue_block(stage0, i0 + 2 * S::kTileQ);
-        compute_block(stage1, i0 + S::kTileQ);
+    for (int blk = 0; blk < n_blocks; blk += 2) {        // n_blocks is even
+        step(blk, set_a, set_b);
+        step(blk + 1, set_b, set_a);
     }
+    // the last block's dV^T / dK^T products
+#pragma unroll
+    for (int idx = 0; idx < kSteps; idx++) late_products(set_b, idx);
+    wait_vmcnt<0>();      // redundant tail prefetches must not outlive the workgroup's LDS
 
     // ---- epilogue: lane <-> key my_j, register r of block db <-> column 32db + 8*(r/4) + 4h + r%4
     bf16* dKr = dK + head + (size_t)my_j * D;
@@ -243,6 +339,8 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
             bf16x2 f = cvt2(dv_acc[db][4 * g + 2], dv_acc[db][4 * g + 3]);
             *(bf16x4*)(dVr + col) = __builtin_shufflevector(e, f, 0, 1, 2, 3);
         }
+    __builtin_amdgcn_s_barrier();      // every wave is done with the ring before the next pass refills it
+    }   // pass
 }
 
 template <int D, bool CAUSAL>
@@ -252,7 +350,7 @@ static hipError_t launch_dkdv_t(const void* q, const void* k, const void* v, con
 {
     using S = DkdvShape<D>;
     const int num_kv_tiles = N / S::kTileKV;
-    const int total = B * H * num_kv_tiles;
+    const int total = B * H * (CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles);
     hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL>), dim3(total), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
                        (bf16*)dk, (bf16*)dv, N, num_kv_tiles, total, scale);
@@ -301,14 +399,19 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
     const int l32 = lane & 31;
     const int h = lane >> 5;
 
+    // Work unit: one query tile, or, when causal, the pair (last - u, u): tile t streams t+1 blocks
+    // of 128 keys, so every pair carries the same work and the launch is balanced.
+    const int units = CAUSAL ? (num_q_tiles + 1) / 2 : num_q_tiles;
     const int logical = xcd_remap(blockIdx.x, total_wg);
-    const int bh = logical / num_q_tiles;
-    int qt = logical % num_q_tiles;
-    if (CAUSAL) qt = num_q_tiles - 1 - qt;        // heavy (late) query tiles first
-
+    const int bh = logical / units;
+    const int unit = logical % units;
     const size_t head = (size_t)bh * N * D;
     const bf16* Kh = K + head;
     const bf16* Vh = V + head;
+#pragma unroll 1
+    for (int pass = 0; pass < (CAUSAL ? 2 : 1); pass++) {
+    const int qt = pass == 0 ? num_q_tiles - 1 - unit : unit;
+    if (pass == 1 && qt == num_q_tiles - 1 - unit) break;   // odd tile count: the middle tile has no partner
     const int q0 = qt * S::kTileQ + wave * 32;
     const int my_q = q0 + l32;
     const float c = scale * kLog2e;
@@ -425,6 +528,7 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
             bf16x2 hi = cvt2(dq_acc[db][4 * g + 2] * scale, dq_acc[db][4 * g + 3] * scale);
             *(bf16x4*)(dQr + 32 * db + 8 * g + 4 * h) = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
         }
+    }   // pass (the loop above ends with a barrier, so both stages are free again)
 }
 
 template <int D, bool CAUSAL>
@@ -434,7 +538,7 @@ static hipError_t launch_dq_t(const void* q, const void* k, const void* v, const
 {
     using S = DqShape<D>;
     const int num_q_tiles = N / S::kTileQ;
-    const int total = B * H * num_q_tiles;
+    const int total = B * H * (CAUSAL ? (num_q_tiles + 1) / 2 : num_q_tiles);
     hipLaunchKernelGGL((attn_bwd_dq_kernel<D, CAUSAL>), dim3(total), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
                        (bf16*)dq, N, num_q_tiles, total, scale);
