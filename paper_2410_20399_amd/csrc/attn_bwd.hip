@@ -81,6 +81,8 @@ struct DkdvShape {
     static constexpr int kStageBytes = 2 * kQTileBytes + 256;      // Q, dO, LSE[32], Delta[32]; a multiple of 256
     static constexpr int kQLoads = kTileQ * kChunksPerRow / kThreads;   // per thread, per tensor
     static constexpr int kLoadsPerBlock = 2 * kQLoads;  // per thread (wave 0 issues one more, for the statistics)
+    static constexpr int kEpiPitch = kRowBytes + 8;     // row pitch of the epilogue staging tile: the odd multiple of 8 bytes spreads
+                                                        // both the 8-byte column-piece writes and the row reads over the banks
 };
 
 // Chunk swizzle of every row-major bf16 tile in the backward kernels (rows of D elements): spreads
@@ -99,15 +101,22 @@ template <int D> __device__ __forceinline__ int swz(int row) {
 //     phase 3  dV^T, dK^T MFMAs from the transposed fragments; meanwhile the row fragments of the
 //              NEXT block are read from LDS
 // and the query blocks themselves arrive by direct global->LDS loads issued three blocks ahead.
+//
+// Nothing hides a workgroup's start-up and wind-down either, so the launch is persistent: one
+// workgroup per compute unit walks the key tiles v = blockIdx.x, blockIdx.x + gridDim.x, ... and
+// the query-block stream never stops: the loads issued during the last blocks of one key tile
+// already fetch the first blocks of the next, and the next tile's K, V fragments are requested
+// before the current tile's results are stored.
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 1)
 void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                           const bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
                           bf16* __restrict__ dK, bf16* __restrict__ dV,
-                          int N, int num_kv_tiles, int total_wg, float scale)
+                          int N, int num_kv_tiles, int total_units, float scale)
 {
     using S = DkdvShape<D>;
     __shared__ __attribute__((aligned(1024))) char ring[S::kStages * S::kStageBytes];
+    __shared__ __attribute__((aligned(16))) char epi[S::kWaves * 32 * S::kEpiPitch];   // per-wave staging of the dK / dV tile
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -116,30 +125,27 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     const int h = lane >> 5;
     const int j16 = lane & 15;
     const int ghalf = (lane >> 4) & 1;
-
-    // Work unit of a workgroup: one key tile, or, when causal, the pair (u, last - u): tile u loops
-    // over (N - 128u)/32 query blocks, so every pair carries the same work and the launch is balanced.
-    const int units = CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles;
-    const int logical = xcd_remap(blockIdx.x, total_wg);
-    const int bh = logical / units;
-    const int unit = logical % units;
-    const size_t head = (size_t)bh * N * D;
-#pragma unroll 1
-    for (int pass = 0; pass < (CAUSAL ? 2 : 1); pass++) {
-    const int kt = pass == 0 ? unit : num_kv_tiles - 1 - unit;
-    if (pass == 1 && kt == unit) break;            // odd tile count: the middle tile has no partner
-    const int j0 = kt * S::kTileKV;
-    const int jw0 = j0 + wave * 32;                // first key of this wave
-    const int my_j = jw0 + l32;
-
-    const bf16* Qh = Q + head;
-    const bf16* dOh = dO + head;
-    const float* LSEh = LSE + (size_t)bh * N;
-    const float* Deltah = Delta + (size_t)bh * N;
-
     const float c = scale * kLog2e;
-    const int i_begin = CAUSAL ? j0 : 0;
-    const int n_blocks = (N - i_begin) / S::kTileQ;
+
+    // Work unit: one key tile, or, when causal, the pair (u, last - u): tile u loops over
+    // (N - 128u)/32 query blocks, so every pair carries the same work and the static schedule is
+    // balanced.  A "pass" is one key tile; (vu, half) names the pass `half` of unit vu.
+    const int units = CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles;
+    auto pass_tile = [&](int vu, int half, int& bh, int& kt) {
+        const int logical = xcd_remap(vu, total_units);
+        bh = logical / units;
+        const int unit = logical % units;
+        kt = half == 0 ? unit : num_kv_tiles - 1 - unit;
+    };
+    // the pass after (vu, half) in this workgroup's walk; vu >= total_units means "none"
+    auto next_pass = [&](int& vu, int& half) {
+        if (CAUSAL && half == 0) {
+            const int unit = xcd_remap(vu, total_units) % units;
+            if (num_kv_tiles - 1 - unit != unit) { half = 1; return; }   // (odd tile count: the middle tile has no partner)
+        }
+        vu += gridDim.x;
+        half = 0;
+    };
 
     // ---- query-block prefetch: Q, dO rows (swizzled), LSE and Delta of 32 queries
     int q_src[S::kQLoads];
@@ -149,34 +155,43 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         int row = s / S::kChunksPerRow, pc = s % S::kChunksPerRow;
         q_src[it] = row * D + ((pc ^ swz<D>(row)) * 8);
     }
-    // Past the last block the last one is fetched again (into a stage nobody reads), so that every
-    // call issues the same number of loads and the vmcnt waits below can count them.
-    auto issue_block = [&](int blk) {
-        const int st = blk & (S::kStages - 1);
-        const int i0 = i_begin + (blk < n_blocks ? blk : n_blocks - 1) * S::kTileQ;
-        char* base = ring + st * S::kStageBytes;
+    // Producer side of the ring: a cursor over the query blocks of this workgroup's passes, in the
+    // order the passes consume them.  Every call issues the same number of loads (the vmcnt waits
+    // below count them); once the walk is exhausted it fetches `spare_row`'s block again into a
+    // stage nobody reads.
+    int p_vu = blockIdx.x, p_half = 0, p_blk = 0, p_nblocks = 0;
+    size_t p_row0 = 0;                      // bh * N + i_begin of the producer's pass
+    size_t spare_row = 0;
+    int p_count = 0;                        // blocks issued so far (selects the ring stage)
+    auto producer_open = [&]() {            // set the cursor to the first block of pass (p_vu, p_half)
+        int bh, kt;
+        pass_tile(p_vu, p_half, bh, kt);
+        const int i_begin = CAUSAL ? kt * S::kTileKV : 0;
+        p_row0 = (size_t)bh * N + i_begin;
+        p_nblocks = (N - i_begin) / S::kTileQ;
+        p_blk = 0;
+    };
+    auto issue_next = [&]() {
+        const bool live = p_vu < total_units;
+        const size_t row = live ? p_row0 + (size_t)p_blk * S::kTileQ : spare_row;
+        char* base = ring + (p_count & (S::kStages - 1)) * S::kStageBytes;
 #pragma unroll
         for (int it = 0; it < S::kQLoads; it++)
-            load_global_to_lds16_untracked(Qh + (size_t)i0 * D + q_src[it], base + it * (S::kThreads * 16) + wave * 1024);
+            load_global_to_lds16_untracked(Q + row * D + q_src[it], base + it * (S::kThreads * 16) + wave * 1024);
 #pragma unroll
         for (int it = 0; it < S::kQLoads; it++)
-            load_global_to_lds16_untracked(dOh + (size_t)i0 * D + q_src[it],
+            load_global_to_lds16_untracked(dO + row * D + q_src[it],
                                            base + S::kQTileBytes + it * (S::kThreads * 16) + wave * 1024);
-        if (wave == 0 && lane < 16) {   // 8 lanes fetch LSE[i0..i0+31], 8 lanes Delta[i0..i0+31]
-            const float* src = (lane < 8) ? (LSEh + i0 + lane * 4) : (Deltah + i0 + (lane - 8) * 4);
+        if (wave == 0 && lane < 16) {   // 8 lanes fetch LSE[row..row+31], 8 lanes Delta[row..row+31]
+            const float* src = (lane < 8) ? (LSE + row + lane * 4) : (Delta + row + (lane - 8) * 4);
             load_global_to_lds16_untracked(src, base + 2 * S::kQTileBytes);
         }
+        p_count++;
+        if (live && ++p_blk == p_nblocks) {
+            next_pass(p_vu, p_half);
+            if (p_vu < total_units) producer_open();
+        }
     };
-#pragma unroll
-    for (int b = 0; b < S::kAhead; b++) issue_block(b);
-
-    // ---- K, V fragments of this wave's 32 keys (B operands of S = Q K^T and dP = dO V^T)
-    bf16x8 kf[D / 16], vf[D / 16];
-#pragma unroll
-    for (int kb = 0; kb < D / 16; kb++) {
-        kf[kb] = *(const bf16x8*)(K + head + (size_t)my_j * D + kb * 16 + h * 8);
-        vf[kb] = *(const bf16x8*)(V + head + (size_t)my_j * D + kb * 16 + h * 8);
-    }
 
     // ---- per-lane LDS offsets
     // row operand (A of S and dP): row l32, logical chunk 2*kb + h
@@ -185,13 +200,47 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     const int trq_row = 4 * h + (j16 >> 2);
     const int trq_lane = trq_row * S::kRowBytes + (((2 * ghalf + ((j16 & 3) >> 1)) ^ swz<D>(trq_row)) << 4) + ((j16 & 1) << 3);
 
+    constexpr int kSteps = D / 16;          // MFMA steps of S / dP; also 2 * (D/32) steps of dV^T / dK^T
+    bf16x8 kf[D / 16], vf[D / 16];          // K, V fragments of this wave's 32 keys (B operands of S = Q K^T and dP = dO V^T)
+    auto load_kv = [&](int bh, int kt) {
+        const size_t row = (size_t)bh * N + kt * S::kTileKV + wave * 32 + l32;
+#pragma unroll
+        for (int kb = 0; kb < D / 16; kb++) {
+            kf[kb] = *(const bf16x8*)(K + row * D + kb * 16 + h * 8);
+            vf[kb] = *(const bf16x8*)(V + row * D + kb * 16 + h * 8);
+        }
+    };
+
+    int c_vu = blockIdx.x, c_half = 0;      // consumer side: the pass being computed (the grid never exceeds the unit count)
+    int c_count = 0;                        // blocks consumed so far (selects the ring stage)
+    {
+        int bh, kt;
+        pass_tile(c_vu, c_half, bh, kt);
+        producer_open();
+        spare_row = p_row0;
+#pragma unroll
+        for (int b = 0; b < S::kAhead; b++) issue_next();
+        load_kv(bh, kt);
+    }
+
+#pragma unroll 1
+    while (c_vu < total_units) {
+    int bh, kt;
+    pass_tile(c_vu, c_half, bh, kt);
+    const size_t head = (size_t)bh * N * D;
+    const int j0 = kt * S::kTileKV;
+    const int jw0 = j0 + wave * 32;                // first key of this wave
+    const int my_j = jw0 + l32;
+    const int i_begin = CAUSAL ? j0 : 0;
+    const int n_blocks = (N - i_begin) / S::kTileQ;
+    spare_row = (size_t)bh * N + i_begin;
+
     f32x16 dk_acc[D / 32], dv_acc[D / 32];
 #pragma unroll
     for (int db = 0; db < D / 32; db++)
 #pragma unroll
         for (int r = 0; r < 16; r++) { dk_acc[db][r] = 0.f; dv_acc[db][r] = 0.f; }
 
-    constexpr int kSteps = D / 16;          // MFMA steps of S / dP; also 2 * (D/32) steps of dV^T / dK^T
     bf16x8 rq[kSteps], rdo[kSteps];         // row fragments of the block about to be computed
     // transposed fragments [ks * (D/32) + db] and bf16 P / dS of a block; two sets, because the
     // dV^T / dK^T products of a block are issued one iteration late (see the loop)
@@ -227,29 +276,29 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         dk_acc[db] = mfma32(L.tq[idx], L.dsb[ks], dk_acc[db]);
     };
 
-    // Every global load so far (K, V fragments and blocks 0..2) completes here.  The empty asm
-    // statements pin the fragment loads above this point (the compiler would otherwise sink them to
-    // their first use inside the loop and wait for them there, draining the prefetch every
-    // iteration): inside the loop the only waits on the vector memory counter are the explicit ones,
-    // which leave the newest prefetch in flight.
+    // Every global load so far (this pass's K, V fragments, its first blocks, the previous pass's
+    // stores) completes here.  The empty asm statements pin the fragment loads above this point (the
+    // compiler would otherwise sink them to their first use inside the loop and wait for them there,
+    // draining the prefetch every iteration): inside the loop the only waits on the vector memory
+    // counter are the explicit ones, which leave the newest prefetch in flight.
 #pragma unroll
     for (int kb = 0; kb < D / 16; kb++) asm volatile("" : "+v"(kf[kb]), "+v"(vf[kb]));
     wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();           // blocks 0..2 landed and visible
+    __builtin_amdgcn_s_barrier();           // the pass's first blocks landed and visible
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kb = 0; kb < kSteps; kb++) read_rows(ring, kb);
+    for (int kb = 0; kb < kSteps; kb++) read_rows(ring + (c_count & (S::kStages - 1)) * S::kStageBytes, kb);
 
     // One query block.  cur receives this block's transposed fragments and bf16 P / dS; prev holds
     // those of the previous block, whose dV^T / dK^T products run here, interleaved with this block's
     // vector-ALU work (P, dS), so that the matrix pipe has work while the ALU is busy.
-    auto step = [&](int blk, Late& cur, const Late& prev) {
+    auto step = [&](auto masked, int blk, Late& cur, const Late& prev) {
         const int i0 = i_begin + blk * S::kTileQ;
-        const char* qs = ring + (blk & (S::kStages - 1)) * S::kStageBytes;
-        const char* qs_next = ring + ((blk + 1) & (S::kStages - 1)) * S::kStageBytes;
+        const char* qs = ring + ((c_count + blk) & (S::kStages - 1)) * S::kStageBytes;
+        const char* qs_next = ring + ((c_count + blk + 1) & (S::kStages - 1)) * S::kStageBytes;
         const f32x4* stat = (const f32x4*)(qs + 2 * S::kQTileBytes);
 
-        issue_block(blk + S::kAhead);       // into the stage of block blk-1, which every wave has left
+        issue_next();                       // into the stage of the previous block, which every wave has left
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- phase 1: S = Q K^T, dP = dO V^T; read this block's transposed fragments and statistics
@@ -269,10 +318,10 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         // (dV^T += dO^T P, dK^T += Q^T dS) and with the reads of the next block's row fragments
         // (that block landed before the barrier that ended the previous iteration).
         // register r <-> query i0 + 8*(r/4) + 4h + r%4, lane <-> key my_j
-        // Only the first few blocks of a causal tile cross the diagonal: they push the masked scores
-        // to -inf in a branch of their own (P = 2^-inf = 0), so that the common case carries no
-        // compare / select per element.
-        if (CAUSAL && (i0 < jw0 + 31)) {
+        // Only the first four blocks of a causal tile touch the diagonal: they run as a loop of
+        // their own that pushes the masked scores to -inf (P = 2^-inf = 0), so that the main loop
+        // carries no compare / select per element.
+        if (decltype(masked)::value) {
 #pragma unroll
             for (int r = 0; r < 16; r++)
                 if (i0 + 8 * (r >> 2) + 4 * h + (r & 3) < my_j) s[r] = -INFINITY;
@@ -296,7 +345,7 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
 #pragma unroll
         for (int idx = 0; idx < kSteps; idx++) {
             late_products(prev, idx);
-            read_rows(qs_next, idx);        // (after the last block: stale data, never used)
+            read_rows(qs_next, idx);        // (the next block in the stream: the next pass's first one after this pass's last)
         }
         // schedule: one MFMA, then a slice of the vector work and one LDS read
 #pragma unroll
@@ -306,8 +355,9 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
         }
 
-        // block blk+2 (issued two iterations ago) must have landed before the next iteration reads its
-        // rows; the newer prefetches may stay in flight (wave 0 issues one more load per block)
+        // the block two ahead in the stream (issued two iterations ago) must have landed before the
+        // next iteration reads its rows; the newer prefetches may stay in flight (wave 0 issues one
+        // more load per block)
         if (wave == 0) wait_vmcnt<(S::kAhead - 2) * (S::kLoadsPerBlock + 1)>();
         else wait_vmcnt<(S::kAhead - 2) * S::kLoadsPerBlock>();
         __builtin_amdgcn_sched_barrier(0);
@@ -315,32 +365,63 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    for (int blk = 0; blk < n_blocks; blk += 2) {        // n_blocks is even
-        step(blk, set_a, set_b);
-        step(blk + 1, set_b, set_a);
+    // n_blocks is a multiple of 4; when causal, blocks 0..3 are the ones that touch the diagonal
+    int blk = 0;
+    if (CAUSAL) {
+#pragma unroll 1
+        for (; blk < 4; blk += 2) {
+            step(std::true_type{}, blk, set_a, set_b);
+            step(std::true_type{}, blk + 1, set_b, set_a);
+        }
+    }
+#pragma unroll 1
+    for (; blk < n_blocks; blk += 2) {
+        step(std::false_type{}, blk, set_a, set_b);
+        step(std::false_type{}, blk + 1, set_b, set_a);
+    }
+    c_count += n_blocks;
+
+    // The next pass's K, V fragments are requested now, so that they travel while this pass's last
+    // products and its stores run (S and dP are done with the old fragments).
+    next_pass(c_vu, c_half);
+    if (c_vu < total_units) {
+        int nbh, nkt;
+        pass_tile(c_vu, c_half, nbh, nkt);
+        load_kv(nbh, nkt);
     }
     // the last block's dV^T / dK^T products
 #pragma unroll
     for (int idx = 0; idx < kSteps; idx++) late_products(set_b, idx);
-    wait_vmcnt<0>();      // redundant tail prefetches must not outlive the workgroup's LDS
 
-    // ---- epilogue: lane <-> key my_j, register r of block db <-> column 32db + 8*(r/4) + 4h + r%4
-    bf16* dKr = dK + head + (size_t)my_j * D;
-    bf16* dVr = dV + head + (size_t)my_j * D;
+    // ---- epilogue.  In accumulator layout a lane holds 4 consecutive columns of ONE key row
+    // (lane <-> key my_j, register r of block db <-> column 32db + 8*(r/4) + 4h + r%4), so storing
+    // from there would touch 32 rows per instruction.  Each wave instead turns its 32 x D tile
+    // around in a private LDS buffer and stores whole rows, 16 bytes per lane.
+    char* my_epi = epi + wave * (32 * S::kEpiPitch);
+    auto store_tile = [&](const f32x16 (&acc)[D / 32], float mul, bf16* dst) {   // dst: first row of this wave's tile
 #pragma unroll
-    for (int db = 0; db < D / 32; db++)
+        for (int db = 0; db < D / 32; db++)
 #pragma unroll
-        for (int g = 0; g < 4; g++) {
-            const int col = 32 * db + 8 * g + 4 * h;
-            bf16x2 a = cvt2(dk_acc[db][4 * g] * scale, dk_acc[db][4 * g + 1] * scale);
-            bf16x2 b = cvt2(dk_acc[db][4 * g + 2] * scale, dk_acc[db][4 * g + 3] * scale);
-            *(bf16x4*)(dKr + col) = __builtin_shufflevector(a, b, 0, 1, 2, 3);
-            bf16x2 e = cvt2(dv_acc[db][4 * g], dv_acc[db][4 * g + 1]);
-            bf16x2 f = cvt2(dv_acc[db][4 * g + 2], dv_acc[db][4 * g + 3]);
-            *(bf16x4*)(dVr + col) = __builtin_shufflevector(e, f, 0, 1, 2, 3);
+            for (int g = 0; g < 4; g++) {
+                bf16x2 a = cvt2(acc[db][4 * g] * mul, acc[db][4 * g + 1] * mul);
+                bf16x2 b = cvt2(acc[db][4 * g + 2] * mul, acc[db][4 * g + 3] * mul);
+                *(bf16x4*)(my_epi + l32 * S::kEpiPitch + (32 * db + 8 * g + 4 * h) * 2) = __builtin_shufflevector(a, b, 0, 1, 2, 3);
+            }
+        constexpr int kLanesPerRow = D * 2 / 16;
+        constexpr int kRowsPerStore = 64 / kLanesPerRow;
+        const int sub_row = lane / kLanesPerRow, col16 = lane % kLanesPerRow;
+#pragma unroll
+        for (int i = 0; i < 32 / kRowsPerStore; i++) {
+            const int row = i * kRowsPerStore + sub_row;
+            const char* src = my_epi + row * S::kEpiPitch + col16 * 16;
+            const bf16x4 lo = *(const bf16x4*)src, hi = *(const bf16x4*)(src + 8);
+            *(bf16x8*)(dst + (size_t)row * D + col16 * 8) = concat(lo, hi);
         }
-    __builtin_amdgcn_s_barrier();      // every wave is done with the ring before the next pass refills it
+    };
+    store_tile(dk_acc, scale, dK + head + (size_t)jw0 * D);
+    store_tile(dv_acc, 1.0f, dV + head + (size_t)jw0 * D);
     }   // pass
+    wait_vmcnt<0>();      // the spare prefetches of the last blocks must not outlive the workgroup's LDS
 }
 
 template <int D, bool CAUSAL>
@@ -350,10 +431,14 @@ static hipError_t launch_dkdv_t(const void* q, const void* k, const void* v, con
 {
     using S = DkdvShape<D>;
     const int num_kv_tiles = N / S::kTileKV;
-    const int total = B * H * (CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles);
-    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL>), dim3(total), dim3(S::kThreads), 0, stream,
+    const int total_units = B * H * (CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles);
+    int cus = 0;
+    hipError_t e = compute_unit_count(&cus);
+    if (e != hipSuccess) return e;
+    const int grid = total_units < cus ? total_units : cus;     // one resident workgroup per compute unit
+    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL>), dim3(grid), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
-                       (bf16*)dk, (bf16*)dv, N, num_kv_tiles, total, scale);
+                       (bf16*)dk, (bf16*)dv, N, num_kv_tiles, total_units, scale);
     return hipGetLastError();
 }
 
@@ -464,41 +549,47 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
         const int j0 = tile * S::kTileKV;
         if (CAUSAL && j0 > q0 + 31) return;          // every key of the tile is masked for this wave
         const char* vs = ks + S::kTileBytes;
-        f32x16 s[2], dp[2];
+        const bool diag = CAUSAL && (j0 + S::kTileKV - 1 > q0);   // the tile crosses this wave's diagonal
+        // The tile is processed in two halves of 32 keys, so that only one half's S^T / dP^T
+        // accumulators are live at a time.
 #pragma unroll
         for (int b = 0; b < 2; b++) {
+            f32x16 s, dp;
 #pragma unroll
-            for (int r = 0; r < 16; r++) { s[b][r] = 0.f; dp[b][r] = 0.f; }
+            for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
             for (int kb = 0; kb < D / 16; kb++) {
                 const int off = (row_lane ^ ((2 * kb) << 4)) + b * 32 * S::kRowBytes;
-                s[b] = mfma32(lds_read_b128(ks, off), qf[kb], s[b]);
-                dp[b] = mfma32(lds_read_b128(vs, off), dof[kb], dp[b]);
+                s = mfma32(lds_read_b128(ks, off), qf[kb], s);
+                dp = mfma32(lds_read_b128(vs, off), dof[kb], dp);
             }
-        }
-        // P^T and dS^T: lane <-> query my_q, register r of block b <-> key j0 + 32b + 8*(r/4) + 4h + r%4
-        const bool diag = CAUSAL && (j0 + S::kTileKV - 1 > q0);
+            // P^T and dS^T: lane <-> query my_q, register r <-> key j0 + 32b + 8*(r/4) + 4h + r%4.
+            // Only a tile on the diagonal needs the mask: it pushes the masked scores to -inf in a
+            // branch of its own (P = 2^-inf = 0), so the common case carries no compare / select.
+            if (diag) {
 #pragma unroll
-        for (int b = 0; b < 2; b++)
+                for (int r = 0; r < 16; r++)
+                    if (j0 + 32 * b + 8 * (r >> 2) + 4 * h + (r & 3) > my_q) s[r] = -INFINITY;
+            }
 #pragma unroll
             for (int r = 0; r < 16; r++) {
-                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[b][r], c, -lse2));
-                if (diag && (j0 + 32 * b + 8 * (r >> 2) + 4 * h + (r & 3) > my_q)) p = 0.f;
-                s[b][r] = p * (dp[b][r] - delta);
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -lse2));
+                s[r] = p * (dp[r] - delta);
             }
-        // dQ^T += K^T dS^T, 16 keys per MFMA
+            // dQ^T += K^T dS^T, 16 keys per MFMA
 #pragma unroll
-        for (int kk = 0; kk < 4; kk++) {
-            const int b = kk >> 1, r0 = 8 * (kk & 1);
-            bf16x8 dsb = cvt8(s[b][r0 + 0], s[b][r0 + 1], s[b][r0 + 2], s[b][r0 + 3],
-                              s[b][r0 + 4], s[b][r0 + 5], s[b][r0 + 6], s[b][r0 + 7]);
+            for (int k2 = 0; k2 < 2; k2++) {
+                const int kk = 2 * b + k2, r0 = 8 * k2;
+                bf16x8 dsb = cvt8(s[r0 + 0], s[r0 + 1], s[r0 + 2], s[r0 + 3],
+                                  s[r0 + 4], s[r0 + 5], s[r0 + 6], s[r0 + 7]);
 #pragma unroll
-            for (int db = 0; db < D / 32; db++) {
-                const int row_off = 16 * kk * S::kRowBytes;
-                const int x0 = (4 * db) << 4, x1 = ((4 * db) ^ 2) << 4;
-                bf16x4 a0 = lds_read_tr16(ks, (tr_lane ^ x0) + row_off);
-                bf16x4 a1 = lds_read_tr16(ks, (tr_lane ^ x1) + row_off + 8 * S::kRowBytes);
-                dq_acc[db] = mfma32(concat(a0, a1), dsb, dq_acc[db]);
+                for (int db = 0; db < D / 32; db++) {
+                    const int row_off = 16 * kk * S::kRowBytes;
+                    const int x0 = (4 * db) << 4, x1 = ((4 * db) ^ 2) << 4;
+                    bf16x4 a0 = lds_read_tr16(ks, (tr_lane ^ x0) + row_off);
+                    bf16x4 a1 = lds_read_tr16(ks, (tr_lane ^ x1) + row_off + 8 * S::kRowBytes);
+                    dq_acc[db] = mfma32(concat(a0, a1), dsb, dq_acc[db]);
+                }
             }
         }
     };

@@ -5,6 +5,14 @@
 
 namespace tk {
 
+// Compute units of the current device (persistent kernels size their grid by it).
+inline hipError_t compute_unit_count(int* cus) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    return hipDeviceGetAttribute(cus, hipDeviceAttributeMultiprocessorCount, dev);
+}
+
 hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                            int B, int H, int N, int D, int causal, float scale, hipStream_t stream);
 
