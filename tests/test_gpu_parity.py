@@ -49,6 +49,9 @@ SMALL = [
     (1, 1, 128, 64, False), (1, 1, 128, 64, True), (1, 1, 128, 128, False), (1, 1, 128, 128, True),
     (1, 3, 384, 64, True), (2, 3, 384, 128, False), (1, 2, 640, 128, True), (2, 4, 256, 64, False),
     (1, 1, 1024, 128, True), (1, 5, 896, 64, True), (1, 8, 512, 128, False),
+    # more work units than compute units: the persistent backward workgroups walk several key
+    # tiles each, across heads, including an unpaired middle tile and a unit count not divisible by 8
+    (2, 84, 384, 64, True), (1, 130, 640, 128, True), (1, 70, 512, 128, False),
 ]
 
 
