@@ -33,6 +33,7 @@ def main():
     ap.add_argument("--workload", type=int, default=6, help="index into workloads.WORKLOADS (default: the target shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle sample")
+    ap.add_argument("--no-mfma-probe", action="store_true", help="skip the bare-MFMA ceiling measurement")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy a few times, so that a counter run of this same "
                          "command can scale FETCH_SIZE / WRITE_SIZE by what they read for a known transfer")
@@ -146,6 +147,31 @@ def main():
         out["roofline"] = {"kernel": "attn_fwd_kernel", "bound": "mfma", "achieved": round(fwd_tflops, 2),
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": round(fwd_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+
+    # ---- what the matrix pipe sustains on its own: a bare MFMA stream, one wave per SIMD, timed
+    # with constant operands (few wires toggle, the chip holds a high clock) and with the
+    # workload's own kind of data (normal bf16).  The second figure is the practical ceiling of any
+    # kernel fed with such data; the roofline fractions above stay priced against the published peak.
+    if not args.no_mfma_probe:
+        cus = torch.cuda.get_device_properties(dev).multi_processor_count
+        iters = 4000
+        probe_flops = cus * 4 * iters * 32 * (32 * 32 * 16 * 2)
+        sink = torch.empty(cus * 256, dtype=torch.float32, device=dev)
+        res = {}
+        gen = torch.Generator().manual_seed(20399)
+        for kind in ("constant", "normal"):
+            ops = (torch.ones(16 * 256 * 8) if kind == "constant" else torch.randn(16 * 256 * 8, generator=gen)).to(torch.bfloat16).to(dev)
+            check(attn.tk_mfma_probe(ops, sink, cus, iters, stream), "probe")
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(5):
+                check(attn.tk_mfma_probe(ops, sink, cus, iters, stream), "probe")
+            e1.record(stream)
+            torch.cuda.synchronize()
+            res[kind] = round(probe_flops / (e0.elapsed_time(e1) / 5 * 1e-3) / 1e12, 1)
+        out["mfma_only_tflops"] = {"constant_operands": res["constant"], "normal_operands": res["normal"],
+                                   "note": "bare v_mfma_f32_32x32x16_bf16 stream, one wave per SIMD, whole chip"}
 
     if args.copy_calibration:
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).fill_(1.0)   # 1 GiB

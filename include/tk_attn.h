@@ -122,6 +122,19 @@ int tk_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
                    void* dq,
                    int B, int H, int N, int D, int causal, float scale, void* stream);
 
+/*
+ * Measurement aid, not part of the attention path: a bare stream of the bf16 MFMA that the
+ * attention kernels use, on caller-supplied operand values.  The benchmark times it to report the
+ * matrix-pipe rate the chip sustains with the same kind of data (the clock it holds depends on
+ * the operand values), next to the published peak.
+ *
+ *   operands   : in, device, 16 fragments x 256 lanes x 16 bytes = 65536 bytes of bf16
+ *   sink       : out, device, workgroups * 256 floats (sums of the accumulators; keeps the work alive)
+ *   workgroups : 1..65536 workgroups of 256 threads (one wave per SIMD); the compute-unit count fills the chip once
+ *   iters      : >= 1; every wave issues 32 * iters MFMAs of 32*32*16*2 flops
+ */
+int tk_mfma_probe(const void* operands, float* sink, int workgroups, int iters, void* stream);
+
 /* Human-readable name of a status code (static storage; never NULL). */
 const char* tk_status_string(int status);
 

@@ -22,7 +22,7 @@ TK_ERR_WORKSPACE_TOO_SMALL = -5
 TK_ERR_LAUNCH = -6
 
 EXPORTS = ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
-           "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_status_string", "tk_attn_version")
+           "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
 
 _lib = None
 
@@ -56,6 +56,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.tk_attn_bwd_dkdv.restype = i
     lib.tk_attn_bwd_dq.argtypes = [vp, vp, vp, vp, fp, fp, vp, i, i, i, i, i, f, vp]
     lib.tk_attn_bwd_dq.restype = i
+    lib.tk_mfma_probe.argtypes = [vp, fp, i, i, vp]
+    lib.tk_mfma_probe.restype = i
     lib.tk_status_string.argtypes = [i]
     lib.tk_status_string.restype = ctypes.c_char_p
     lib.tk_attn_version.argtypes = []
@@ -124,6 +126,10 @@ def tk_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, H, N, D, causal, scale
 def tk_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, H, N, D, causal, scale, stream=None) -> int:
     return load_library().tk_attn_bwd_dq(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(delta),
                                          _ptr(dq), B, H, N, D, int(bool(causal)), float(scale), _stream(stream))
+
+
+def tk_mfma_probe(operands, sink, workgroups, iters, stream=None) -> int:
+    return load_library().tk_mfma_probe(_ptr(operands), _ptr(sink), int(workgroups), int(iters), _stream(stream))
 
 
 # ------------------------------------------------------------------ convenience: allocate outputs, raise on error

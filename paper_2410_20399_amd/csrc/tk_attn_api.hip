@@ -117,6 +117,15 @@ int tk_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
     return TK_OK;
 }
 
+int tk_mfma_probe(const void* operands, float* sink, int workgroups, int iters, void* stream)
+{
+    if (!operands || !sink) return TK_ERR_NULL_PTR;
+    if (workgroups < 1 || workgroups > 65536 || iters < 1) return TK_ERR_BAD_DIM;
+    if (!aligned16(operands) || !aligned16(sink)) return TK_ERR_MISALIGNED;
+    hipError_t e = tk::launch_mfma_probe(operands, sink, workgroups, iters, (hipStream_t)stream);
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
 const char* tk_status_string(int status)
 {
     switch (status) {

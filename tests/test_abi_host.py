@@ -125,6 +125,16 @@ def test_stage_entries_reject_bad_arguments(lib):
         assert fn(*([P] * nptr), 1, 1, 128, 96, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
 
 
+def test_mfma_probe_rejects_bad_arguments(lib):
+    from paper_2410_20399_amd import attn as a
+    assert lib.tk_mfma_probe(None, P, 1, 1, None) == a.TK_ERR_NULL_PTR
+    assert lib.tk_mfma_probe(P, None, 1, 1, None) == a.TK_ERR_NULL_PTR
+    assert lib.tk_mfma_probe(ODD, P, 1, 1, None) == a.TK_ERR_MISALIGNED
+    assert lib.tk_mfma_probe(P, P, 0, 1, None) == a.TK_ERR_BAD_DIM
+    assert lib.tk_mfma_probe(P, P, 70000, 1, None) == a.TK_ERR_BAD_DIM
+    assert lib.tk_mfma_probe(P, P, 1, 0, None) == a.TK_ERR_BAD_DIM
+
+
 def test_missing_library_fails_loudly(tmp_path):
     from paper_2410_20399_amd import attn
     saved = attn._lib
