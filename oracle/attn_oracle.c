@@ -34,6 +34,9 @@
  * shapes, rows of P summing to one, LSE against a naive log-sum-exp, closed
  * forms (Q = 0, N = 1, causal row 0, shift and permutation invariances),
  * central finite differences of L for dQ, dK, dV, sum_j dS_ij = 0.
+ * The grouped-query functions at the end of the file are pinned to the
+ * per-head ones (keys/values repeated per group, gradients summed over the
+ * group), to a brute-force numpy softmax and to finite differences.
  *
  * Build: gcc -O2 -fopenmp -shared -fPIC attn_oracle.c -o liboracle_attn.so -lm
  */
@@ -244,6 +247,126 @@ int oracle_attn_ds(const double* q, const double* k, const double* v, const doub
         }
     free(s); free(o_i);
     return 0;
+}
+
+/*
+ * Grouped-query attention (Section 4.1 names it as a supported variant and cites Ainslie et
+ * al. 2023; no formula is printed).  Reading taken: Hq query heads, Hkv key/value heads,
+ * G = Hq / Hkv; query head h attends with key/value head h / G (consecutive query heads form
+ * a group), every head otherwise exactly as in the definition above.  The gradient of a shared
+ * key/value head is the sum over its group's query heads.
+ *   q, d_o, o, dq : [B][Hq][N][D]     k, v, dk, dv : [B][Hkv][N][D]     lse : [B][Hq][N]
+ */
+int oracle_gqa_fwd(const double* q, const double* k, const double* v, double* o, double* lse,
+                   long B, long Hq, long Hkv, long N, long D, int causal, double scale)
+{
+    if (!q || !k || !v || !o || !lse || B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || N <= 0 || D <= 0) return -1;
+    const long G = Hq / Hkv;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double* s = (double*)malloc((size_t)N * sizeof(double));
+        if (!s) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for collapse(2) schedule(dynamic, 16)
+            for (long bh = 0; bh < B * Hq; bh++)
+                for (long i = 0; i < N; i++) {
+                    const long b = bh / Hq, h = bh % Hq;
+                    const long kvh = b * Hkv + h / G;
+                    forward_row(q + (bh * N + i) * D, k + kvh * N * D, v + kvh * N * D, i, N, D, causal, scale, s,
+                                o + (bh * N + i) * D, lse + bh * N + i);
+                }
+            free(s);
+        }
+    }
+    return fail ? -2 : 0;
+}
+
+int oracle_gqa_bwd(const double* q, const double* k, const double* v, const double* d_o,
+                   double* dq, double* dk, double* dv,
+                   long B, long Hq, long Hkv, long N, long D, int causal, double scale)
+{
+    if (!q || !k || !v || !d_o || !dq || !dk || !dv || B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || N <= 0 || D <= 0) return -1;
+    const long G = Hq / Hkv;
+    double* delta = (double*)malloc((size_t)B * Hq * N * sizeof(double));
+    double* lse = (double*)malloc((size_t)B * Hq * N * sizeof(double));
+    if (!delta || !lse) { free(delta); free(lse); return -2; }
+    int fail = 0;
+
+    /* sweep 1: per query row of every query head -> Delta_i, LSE_i, dQ_i */
+#pragma omp parallel
+    {
+        double* s = (double*)malloc((size_t)N * sizeof(double));
+        double* o_i = (double*)malloc((size_t)D * sizeof(double));
+        if (!s || !o_i) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for collapse(2) schedule(dynamic, 16)
+            for (long bh = 0; bh < B * Hq; bh++)
+                for (long i = 0; i < N; i++) {
+                    const long b = bh / Hq, h = bh % Hq;
+                    const double* kh = k + (b * Hkv + h / G) * N * D;
+                    const double* vh = v + (b * Hkv + h / G) * N * D;
+                    const double* do_i = d_o + (bh * N + i) * D;
+                    double lse_i;
+                    forward_row(q + (bh * N + i) * D, kh, vh, i, N, D, causal, scale, s, o_i, &lse_i);
+                    double dl = 0.0;
+                    for (long d = 0; d < D; d++) dl += do_i[d] * o_i[d];
+                    delta[bh * N + i] = dl;
+                    lse[bh * N + i] = lse_i;
+                    double* dq_i = dq + (bh * N + i) * D;
+                    for (long d = 0; d < D; d++) dq_i[d] = 0.0;
+                    long nj = visible(i, N, causal);
+                    for (long j = 0; j < nj; j++) {
+                        double dp = 0.0;
+                        for (long d = 0; d < D; d++) dp += do_i[d] * vh[j * D + d];
+                        double ds = s[j] * (dp - dl);
+                        for (long d = 0; d < D; d++) dq_i[d] += ds * kh[j * D + d];
+                    }
+                    for (long d = 0; d < D; d++) dq_i[d] *= scale;
+                }
+        }
+        free(s); free(o_i);
+    }
+
+    /* sweep 2: per key row of every key/value head, summing over the query heads of its group */
+    if (!fail) {
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+        for (long bk = 0; bk < B * Hkv; bk++)
+            for (long j = 0; j < N; j++) {
+                const long b = bk / Hkv, hk = bk % Hkv;
+                const double* k_j = k + (bk * N + j) * D;
+                const double* v_j = v + (bk * N + j) * D;
+                double* dk_j = dk + (bk * N + j) * D;
+                double* dv_j = dv + (bk * N + j) * D;
+                for (long d = 0; d < D; d++) { dk_j[d] = 0.0; dv_j[d] = 0.0; }
+                for (long g = 0; g < G; g++) {
+                    const long bh = b * Hq + hk * G + g;
+                    const double* qh = q + bh * N * D;
+                    const double* doh = d_o + bh * N * D;
+                    long i0 = causal ? j : 0;
+                    for (long i = i0; i < N; i++) {
+                        double dot = 0.0, dp = 0.0;
+                        for (long d = 0; d < D; d++) {
+                            dot += qh[i * D + d] * k_j[d];
+                            dp += doh[i * D + d] * v_j[d];
+                        }
+                        double p = exp(scale * dot - lse[bh * N + i]);
+                        double ds = p * (dp - delta[bh * N + i]);
+                        for (long d = 0; d < D; d++) {
+                            dv_j[d] += p * doh[i * D + d];
+                            dk_j[d] += ds * qh[i * D + d];
+                        }
+                    }
+                }
+                for (long d = 0; d < D; d++) dk_j[d] *= scale;
+            }
+    }
+    free(delta); free(lse);
+    return fail ? -2 : 0;
 }
 
 int oracle_num_threads(void)

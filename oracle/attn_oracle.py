@@ -29,8 +29,10 @@ def _load():
         lib.oracle_attn_fwd_rows.argtypes = [dp, dp, dp, lp, L, dp, dp, L, L, I, F]
         lib.oracle_attn_bwd.argtypes = [dp, dp, dp, dp, dp, dp, dp, dp, dp, L, L, L, I, F]
         lib.oracle_attn_ds.argtypes = [dp, dp, dp, dp, dp, L, L, L, I, F]
+        lib.oracle_gqa_fwd.argtypes = [dp, dp, dp, dp, dp, L, L, L, L, L, I, F]
+        lib.oracle_gqa_bwd.argtypes = [dp, dp, dp, dp, dp, dp, dp, L, L, L, L, L, I, F]
         for f in (lib.oracle_attn_fwd, lib.oracle_attn_fwd_rows, lib.oracle_attn_bwd,
-                  lib.oracle_attn_ds, lib.oracle_num_threads):
+                  lib.oracle_attn_ds, lib.oracle_gqa_fwd, lib.oracle_gqa_bwd, lib.oracle_num_threads):
             f.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -110,3 +112,42 @@ def attn_ds(q, k, v, d_o, causal: bool, scale: float):
     if rc:
         raise RuntimeError(f"oracle_attn_ds failed: {rc}")
     return ds
+
+
+def _gqa_dims(q, k, v):
+    if q.ndim != 4 or k.ndim != 4 or k.shape != v.shape:
+        raise ValueError("q must be [B, Hq, N, D]; k, v [B, Hkv, N, D]")
+    B, Hq, N, D = q.shape
+    if k.shape[0] != B or k.shape[2:] != (N, D) or Hq % k.shape[1]:
+        raise ValueError("k, v must be [B, Hkv, N, D] with Hkv dividing Hq")
+    return B, Hq, k.shape[1], N, D
+
+
+def gqa_fwd(q, k, v, causal: bool, scale: float):
+    """Grouped-query attention: q [B,Hq,N,D], k, v [B,Hkv,N,D] -> O [B,Hq,N,D], LSE [B,Hq,N] (float64).
+
+    Query head h uses key/value head h // (Hq // Hkv)."""
+    B, Hq, Hkv, N, D = _gqa_dims(q, k, v)
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v)
+    o = np.empty(q.shape, np.float64)
+    lse = np.empty(q.shape[:-1], np.float64)
+    rc = _load().oracle_gqa_fwd(qp, kp, vp, _c(o)[1], _c(lse)[1], B, Hq, Hkv, N, D, int(causal), float(scale))
+    if rc:
+        raise RuntimeError(f"oracle_gqa_fwd failed: {rc}")
+    return o, lse
+
+
+def gqa_bwd(q, k, v, d_o, causal: bool, scale: float):
+    """dQ [B,Hq,N,D], dK, dV [B,Hkv,N,D] (float64): dK, dV summed over each group's query heads."""
+    B, Hq, Hkv, N, D = _gqa_dims(q, k, v)
+    if d_o.shape != q.shape:
+        raise ValueError("d_o must have q's shape")
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v); d_o, dop = _c(d_o)
+    dq = np.empty(q.shape, np.float64)
+    dk = np.empty(k.shape, np.float64)
+    dv = np.empty(k.shape, np.float64)
+    rc = _load().oracle_gqa_bwd(qp, kp, vp, dop, _c(dq)[1], _c(dk)[1], _c(dv)[1],
+                                B, Hq, Hkv, N, D, int(causal), float(scale))
+    if rc:
+        raise RuntimeError(f"oracle_gqa_bwd failed: {rc}")
+    return dq, dk, dv
