@@ -105,7 +105,7 @@ int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta,
                       int B, int H, int N, int D, void* stream);
 
 /*
- * Stage 2: dK and dV (bf16 out), one workgroup per tile of 128 keys.
+ * Stage 2: dK and dV (bf16 out), computed per tile of 128 keys by persistent workgroups.
  *   lse, delta : in, fp32 [B,H,N]
  */
 int tk_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
@@ -121,6 +121,42 @@ int tk_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
                    const float* lse, const float* delta,
                    void* dq,
                    int B, int H, int N, int D, int causal, float scale, void* stream);
+
+/*
+ * Grouped-query attention (Section 4.1 lists it among the supported variants; no formula is
+ * printed, so the usual definition is taken): Hq query heads share Hkv key/value heads, Hkv
+ * dividing Hq, and query head h of a batch entry attends with key/value head h / (Hq / Hkv),
+ * i.e. consecutive query heads form a group.  Everything else is as in the calls above, which
+ * are the Hkv == Hq case of these.
+ *
+ *   q, o, d_o, dq : bf16 [B, Hq, N, D]        k, v, dk, dv : bf16 [B, Hkv, N, D]
+ *   lse, delta    : fp32 [B, Hq, N]
+ *   dk, dv are summed over the query heads of each group (in fp32, inside one workgroup: no atomics).
+ *   workspace for tk_attn_bwd_gqa: tk_attn_bwd_workspace_bytes(B, Hq, N, D) bytes.
+ * TK_ERR_BAD_DIM also covers Hkv < 1, Hkv > Hq and Hq % Hkv != 0.
+ */
+int tk_attn_fwd_gqa(const void* q, const void* k, const void* v,
+                    void* o, float* lse,
+                    int B, int Hq, int Hkv, int N, int D, int causal, float scale,
+                    void* stream);
+
+int tk_attn_bwd_gqa(const void* q, const void* k, const void* v,
+                    const void* o, const void* d_o, const float* lse,
+                    void* dq, void* dk, void* dv,
+                    int B, int Hq, int Hkv, int N, int D, int causal, float scale,
+                    void* workspace, size_t workspace_bytes,
+                    void* stream);
+
+/* Stages 2 and 3 of tk_attn_bwd_gqa (stage 1 is tk_attn_bwd_delta with H = Hq). */
+int tk_attn_bwd_dkdv_gqa(const void* q, const void* k, const void* v, const void* d_o,
+                         const float* lse, const float* delta,
+                         void* dk, void* dv,
+                         int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream);
+
+int tk_attn_bwd_dq_gqa(const void* q, const void* k, const void* v, const void* d_o,
+                       const float* lse, const float* delta,
+                       void* dq,
+                       int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream);
 
 /*
  * Measurement aid, not part of the attention path: a bare stream of the bf16 MFMA that the

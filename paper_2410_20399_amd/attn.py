@@ -22,7 +22,8 @@ TK_ERR_WORKSPACE_TOO_SMALL = -5
 TK_ERR_LAUNCH = -6
 
 EXPORTS = ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
-           "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
+           "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_attn_fwd_gqa", "tk_attn_bwd_gqa", "tk_attn_bwd_dkdv_gqa",
+           "tk_attn_bwd_dq_gqa", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
 
 _lib = None
 
@@ -56,6 +57,14 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.tk_attn_bwd_dkdv.restype = i
     lib.tk_attn_bwd_dq.argtypes = [vp, vp, vp, vp, fp, fp, vp, i, i, i, i, i, f, vp]
     lib.tk_attn_bwd_dq.restype = i
+    lib.tk_attn_fwd_gqa.argtypes = [vp, vp, vp, vp, fp, i, i, i, i, i, i, f, vp]
+    lib.tk_attn_fwd_gqa.restype = i
+    lib.tk_attn_bwd_gqa.argtypes = [vp, vp, vp, vp, vp, fp, vp, vp, vp, i, i, i, i, i, i, f, vp, sz, vp]
+    lib.tk_attn_bwd_gqa.restype = i
+    lib.tk_attn_bwd_dkdv_gqa.argtypes = [vp, vp, vp, vp, fp, fp, vp, vp, i, i, i, i, i, i, f, vp]
+    lib.tk_attn_bwd_dkdv_gqa.restype = i
+    lib.tk_attn_bwd_dq_gqa.argtypes = [vp, vp, vp, vp, fp, fp, vp, i, i, i, i, i, i, f, vp]
+    lib.tk_attn_bwd_dq_gqa.restype = i
     lib.tk_mfma_probe.argtypes = [vp, fp, i, i, vp]
     lib.tk_mfma_probe.restype = i
     lib.tk_status_string.argtypes = [i]
@@ -128,6 +137,30 @@ def tk_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, H, N, D, causal, scale, stre
                                          _ptr(dq), B, H, N, D, int(bool(causal)), float(scale), _stream(stream))
 
 
+def tk_attn_fwd_gqa(q, k, v, o, lse, B, Hq, Hkv, N, D, causal, scale, stream=None) -> int:
+    return load_library().tk_attn_fwd_gqa(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, Hq, Hkv, N, D,
+                                          int(bool(causal)), float(scale), _stream(stream))
+
+
+def tk_attn_bwd_gqa(q, k, v, o, d_o, lse, dq, dk, dv, B, Hq, Hkv, N, D, causal, scale, workspace, workspace_bytes,
+                    stream=None) -> int:
+    return load_library().tk_attn_bwd_gqa(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dq),
+                                          _ptr(dk), _ptr(dv), B, Hq, Hkv, N, D, int(bool(causal)), float(scale),
+                                          _ptr(workspace), int(workspace_bytes), _stream(stream))
+
+
+def tk_attn_bwd_dkdv_gqa(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, N, D, causal, scale, stream=None) -> int:
+    return load_library().tk_attn_bwd_dkdv_gqa(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(delta),
+                                               _ptr(dk), _ptr(dv), B, Hq, Hkv, N, D, int(bool(causal)),
+                                               float(scale), _stream(stream))
+
+
+def tk_attn_bwd_dq_gqa(q, k, v, d_o, lse, delta, dq, B, Hq, Hkv, N, D, causal, scale, stream=None) -> int:
+    return load_library().tk_attn_bwd_dq_gqa(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(delta),
+                                             _ptr(dq), B, Hq, Hkv, N, D, int(bool(causal)), float(scale),
+                                             _stream(stream))
+
+
 def tk_mfma_probe(operands, sink, workgroups, iters, stream=None) -> int:
     return load_library().tk_mfma_probe(_ptr(operands), _ptr(sink), int(workgroups), int(iters), _stream(stream))
 
@@ -188,3 +221,38 @@ def attn_bwd_delta(o, d_o, stream=None):
     if rc != TK_OK:
         raise TkAttnError(rc, "tk_attn_bwd_delta")
     return delta
+
+
+def gqa_fwd(q, k, v, causal: bool, scale: float, stream=None):
+    """Grouped-query forward: q bf16 [B,Hq,N,D], k, v bf16 [B,Hkv,N,D]. Returns (o [B,Hq,N,D], lse [B,Hq,N])."""
+    _check_bf16("q", q)
+    B, Hq, N, D = q.shape
+    Hkv = k.shape[1]
+    _check_bf16("k", k, (B, Hkv, N, D))
+    _check_bf16("v", v, (B, Hkv, N, D))
+    o = torch.empty_like(q)
+    lse = torch.empty((B, Hq, N), dtype=torch.float32, device=q.device)
+    rc = tk_attn_fwd_gqa(q, k, v, o, lse, B, Hq, Hkv, N, D, causal, scale, stream)
+    if rc != TK_OK:
+        raise TkAttnError(rc, "tk_attn_fwd_gqa")
+    return o, lse
+
+
+def gqa_bwd(q, k, v, o, d_o, lse, causal: bool, scale: float, workspace=None, stream=None):
+    """Grouped-query backward. Returns (dq [B,Hq,N,D], dk, dv [B,Hkv,N,D]) bf16."""
+    _check_bf16("q", q)
+    B, Hq, N, D = q.shape
+    Hkv = k.shape[1]
+    _check_bf16("k", k, (B, Hkv, N, D))
+    _check_bf16("v", v, (B, Hkv, N, D))
+    _check_bf16("o", o, q.shape)
+    _check_bf16("d_o", d_o, q.shape)
+    _check_f32("lse", lse, (B, Hq, N))
+    if workspace is None:
+        workspace = alloc_bwd_workspace(B, Hq, N, D, q.device)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    rc = tk_attn_bwd_gqa(q, k, v, o, d_o, lse, dq, dk, dv, B, Hq, Hkv, N, D, causal, scale,
+                         workspace, workspace.numel() * workspace.element_size(), stream)
+    if rc != TK_OK:
+        raise TkAttnError(rc, "tk_attn_bwd_gqa")
+    return dq, dk, dv

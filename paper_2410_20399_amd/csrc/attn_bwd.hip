@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256, 1)
 void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                           const bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
                           bf16* __restrict__ dK, bf16* __restrict__ dV,
-                          int N, int num_kv_tiles, int total_units, float scale)
+                          int N, int num_kv_tiles, int total_units, float scale, int hq, int hkv)
 {
     using S = DkdvShape<D>;
     __shared__ __attribute__((aligned(1024))) char ring[S::kStages * S::kStageBytes];
@@ -130,7 +130,14 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     // Work unit: one key tile, or, when causal, the pair (u, last - u): tile u loops over
     // (N - 128u)/32 query blocks, so every pair carries the same work and the static schedule is
     // balanced.  A "pass" is one key tile; (vu, half) names the pass `half` of unit vu.
+    // Grouped-query attention: a key/value head is shared by `group` consecutive query heads, and a
+    // pass streams the query blocks of all of them, one head after the other, into the same dK, dV
+    // accumulators.  bh below counts key/value heads.
+    const int group = hq / hkv;
     const int units = CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles;
+    auto q_head_row = [&](int bh) {         // first row of the first query head of key/value head bh
+        return (size_t)((bh / hkv) * hq + (bh % hkv) * group) * N;
+    };
     auto pass_tile = [&](int vu, int half, int& bh, int& kt) {
         const int logical = xcd_remap(vu, total_units);
         bh = logical / units;
@@ -159,21 +166,22 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     // order the passes consume them.  Every call issues the same number of loads (the vmcnt waits
     // below count them); once the walk is exhausted it fetches `spare_row`'s block again into a
     // stage nobody reads.
-    int p_vu = blockIdx.x, p_half = 0, p_blk = 0, p_nblocks = 0;
-    size_t p_row0 = 0;                      // bh * N + i_begin of the producer's pass
+    int p_vu = blockIdx.x, p_half = 0, p_blk = 0, p_nblocks = 0, p_g = 0;
+    size_t p_row0 = 0;                      // first streamed row (of the group's first query head) of the producer's pass
     size_t spare_row = 0;
     int p_count = 0;                        // blocks issued so far (selects the ring stage)
     auto producer_open = [&]() {            // set the cursor to the first block of pass (p_vu, p_half)
         int bh, kt;
         pass_tile(p_vu, p_half, bh, kt);
         const int i_begin = CAUSAL ? kt * S::kTileKV : 0;
-        p_row0 = (size_t)bh * N + i_begin;
+        p_row0 = q_head_row(bh) + i_begin;
         p_nblocks = (N - i_begin) / S::kTileQ;
         p_blk = 0;
+        p_g = 0;
     };
     auto issue_next = [&]() {
         const bool live = p_vu < total_units;
-        const size_t row = live ? p_row0 + (size_t)p_blk * S::kTileQ : spare_row;
+        const size_t row = live ? p_row0 + (size_t)p_g * N + (size_t)p_blk * S::kTileQ : spare_row;
         char* base = ring + (p_count & (S::kStages - 1)) * S::kStageBytes;
 #pragma unroll
         for (int it = 0; it < S::kQLoads; it++)
@@ -188,8 +196,11 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         }
         p_count++;
         if (live && ++p_blk == p_nblocks) {
-            next_pass(p_vu, p_half);
-            if (p_vu < total_units) producer_open();
+            p_blk = 0;
+            if (++p_g == group) {
+                next_pass(p_vu, p_half);
+                if (p_vu < total_units) producer_open();
+            }
         }
     };
 
@@ -227,13 +238,13 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     while (c_vu < total_units) {
     int bh, kt;
     pass_tile(c_vu, c_half, bh, kt);
-    const size_t head = (size_t)bh * N * D;
+    const size_t head = (size_t)bh * N * D;        // of the key/value head
     const int j0 = kt * S::kTileKV;
     const int jw0 = j0 + wave * 32;                // first key of this wave
     const int my_j = jw0 + l32;
     const int i_begin = CAUSAL ? j0 : 0;
-    const int n_blocks = (N - i_begin) / S::kTileQ;
-    spare_row = (size_t)bh * N + i_begin;
+    const int n_blocks = (N - i_begin) / S::kTileQ;   // per query head of the group
+    spare_row = q_head_row(bh) + i_begin;
 
     f32x16 dk_acc[D / 32], dv_acc[D / 32];
 #pragma unroll
@@ -365,21 +376,25 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // n_blocks is a multiple of 4; when causal, blocks 0..3 are the ones that touch the diagonal
-    int blk = 0;
-    if (CAUSAL) {
+    // n_blocks is a multiple of 4; when causal, blocks 0..3 of every query head are the ones that
+    // touch the diagonal.  The deferred products run on across the heads of the group.
 #pragma unroll 1
-        for (; blk < 4; blk += 2) {
-            step(std::true_type{}, blk, set_a, set_b);
-            step(std::true_type{}, blk + 1, set_b, set_a);
+    for (int g = 0; g < group; g++) {
+        int blk = 0;
+        if (CAUSAL) {
+#pragma unroll 1
+            for (; blk < 4; blk += 2) {
+                step(std::true_type{}, blk, set_a, set_b);
+                step(std::true_type{}, blk + 1, set_b, set_a);
+            }
         }
-    }
 #pragma unroll 1
-    for (; blk < n_blocks; blk += 2) {
-        step(std::false_type{}, blk, set_a, set_b);
-        step(std::false_type{}, blk + 1, set_b, set_a);
+        for (; blk < n_blocks; blk += 2) {
+            step(std::false_type{}, blk, set_a, set_b);
+            step(std::false_type{}, blk + 1, set_b, set_a);
+        }
+        c_count += n_blocks;
     }
-    c_count += n_blocks;
 
     // The next pass's K, V fragments are requested now, so that they travel while this pass's last
     // products and its stores run (S and dP are done with the old fragments).
@@ -427,29 +442,29 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
 template <int D, bool CAUSAL>
 static hipError_t launch_dkdv_t(const void* q, const void* k, const void* v, const void* d_o,
                                 const float* lse, const float* delta, void* dk, void* dv,
-                                int B, int H, int N, float scale, hipStream_t stream)
+                                int B, int H, int Hkv, int N, float scale, hipStream_t stream)
 {
     using S = DkdvShape<D>;
     const int num_kv_tiles = N / S::kTileKV;
-    const int total_units = B * H * (CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles);
+    const int total_units = B * Hkv * (CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles);
     int cus = 0;
     hipError_t e = compute_unit_count(&cus);
     if (e != hipSuccess) return e;
     const int grid = total_units < cus ? total_units : cus;     // one resident workgroup per compute unit
     hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL>), dim3(grid), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
-                       (bf16*)dk, (bf16*)dv, N, num_kv_tiles, total_units, scale);
+                       (bf16*)dk, (bf16*)dv, N, num_kv_tiles, total_units, scale, H, Hkv);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
                                 const float* lse, const float* delta, void* dk, void* dv,
-                                int B, int H, int N, int D, int causal, float scale, hipStream_t stream)
+                                int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream)
 {
-    if (D == 128) return causal ? launch_dkdv_t<128, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, N, scale, stream)
-                                : launch_dkdv_t<128, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, N, scale, stream);
-    return causal ? launch_dkdv_t<64, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, N, scale, stream)
-                  : launch_dkdv_t<64, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, N, scale, stream);
+    if (D == 128) return causal ? launch_dkdv_t<128, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, N, scale, stream)
+                                : launch_dkdv_t<128, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, N, scale, stream);
+    return causal ? launch_dkdv_t<64, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, N, scale, stream)
+                  : launch_dkdv_t<64, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, N, scale, stream);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -472,7 +487,7 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2)
 void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                         const bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
-                        bf16* __restrict__ dQ, int N, int num_q_tiles, int total_wg, float scale)
+                        bf16* __restrict__ dQ, int N, int num_q_tiles, int total_wg, float scale, int hq, int hkv)
 {
     using S = DqShape<D>;
     __shared__ __attribute__((aligned(1024))) char stage0[S::kStageBytes];
@@ -490,9 +505,11 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
     const int logical = xcd_remap(blockIdx.x, total_wg);
     const int bh = logical / units;
     const int unit = logical % units;
+    // grouped-query attention: query head h of a batch entry reads key/value head h / (hq / hkv)
     const size_t head = (size_t)bh * N * D;
-    const bf16* Kh = K + head;
-    const bf16* Vh = V + head;
+    const size_t kv_head = (size_t)((bh / hq) * hkv + (bh % hq) / (hq / hkv)) * N * D;
+    const bf16* Kh = K + kv_head;
+    const bf16* Vh = V + kv_head;
 #pragma unroll 1
     for (int pass = 0; pass < (CAUSAL ? 2 : 1); pass++) {
     const int qt = pass == 0 ? num_q_tiles - 1 - unit : unit;
@@ -625,25 +642,25 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
 template <int D, bool CAUSAL>
 static hipError_t launch_dq_t(const void* q, const void* k, const void* v, const void* d_o,
                               const float* lse, const float* delta, void* dq,
-                              int B, int H, int N, float scale, hipStream_t stream)
+                              int B, int H, int Hkv, int N, float scale, hipStream_t stream)
 {
     using S = DqShape<D>;
     const int num_q_tiles = N / S::kTileQ;
     const int total = B * H * (CAUSAL ? (num_q_tiles + 1) / 2 : num_q_tiles);
     hipLaunchKernelGGL((attn_bwd_dq_kernel<D, CAUSAL>), dim3(total), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
-                       (bf16*)dq, N, num_q_tiles, total, scale);
+                       (bf16*)dq, N, num_q_tiles, total, scale, H, Hkv);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
                               const float* lse, const float* delta, void* dq,
-                              int B, int H, int N, int D, int causal, float scale, hipStream_t stream)
+                              int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream)
 {
-    if (D == 128) return causal ? launch_dq_t<128, true>(q, k, v, d_o, lse, delta, dq, B, H, N, scale, stream)
-                                : launch_dq_t<128, false>(q, k, v, d_o, lse, delta, dq, B, H, N, scale, stream);
-    return causal ? launch_dq_t<64, true>(q, k, v, d_o, lse, delta, dq, B, H, N, scale, stream)
-                  : launch_dq_t<64, false>(q, k, v, d_o, lse, delta, dq, B, H, N, scale, stream);
+    if (D == 128) return causal ? launch_dq_t<128, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, N, scale, stream)
+                                : launch_dq_t<128, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, N, scale, stream);
+    return causal ? launch_dq_t<64, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, N, scale, stream)
+                  : launch_dq_t<64, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, N, scale, stream);
 }
 
 }  // namespace tk

@@ -45,7 +45,7 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2)
 void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                      bf16* __restrict__ O, float* __restrict__ LSE,
-                     int N, int num_q_tiles, int total_wg, float scale)
+                     int N, int num_q_tiles, int total_wg, float scale, int hq, int hkv)
 {
     using S = FwdShape<D>;
     // One array per ring stage: distinct LDS objects let the compiler see that reads of the stage
@@ -66,10 +66,12 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
     int qt = logical % num_q_tiles;
     if (CAUSAL) qt = num_q_tiles - 1 - qt;
 
+    // grouped-query attention: query head h of a batch entry reads key/value head h / (hq / hkv)
     const size_t head = (size_t)bh * N * D;
+    const size_t kv_head = (size_t)((bh / hq) * hkv + (bh % hq) / (hq / hkv)) * N * D;
     const bf16* Qh = Q + head;
-    const bf16* Kh = K + head;
-    const bf16* Vh = V + head;
+    const bf16* Kh = K + kv_head;
+    const bf16* Vh = V + kv_head;
     const int q0 = qt * S::kTileQ + wave * 32;   // first query row of this wave
     const int my_q = q0 + l32;
 
@@ -238,7 +240,7 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
 
 template <int D, bool CAUSAL>
 static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, void* o, float* lse,
-                               int B, int H, int N, float scale, hipStream_t stream)
+                               int B, int H, int Hkv, int N, float scale, hipStream_t stream)
 {
     using S = FwdShape<D>;
     auto kern = attn_fwd_kernel<D, CAUSAL>;
@@ -246,17 +248,17 @@ static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, void
     const int total = B * H * num_q_tiles;
     hipLaunchKernelGGL(kern, dim3(total), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, lse,
-                       N, num_q_tiles, total, scale);
+                       N, num_q_tiles, total, scale, H, Hkv);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
-                           int B, int H, int N, int D, int causal, float scale, hipStream_t stream)
+                           int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream)
 {
-    if (D == 128) return causal ? launch_fwd_t<128, true>(q, k, v, o, lse, B, H, N, scale, stream)
-                                : launch_fwd_t<128, false>(q, k, v, o, lse, B, H, N, scale, stream);
-    return causal ? launch_fwd_t<64, true>(q, k, v, o, lse, B, H, N, scale, stream)
-                  : launch_fwd_t<64, false>(q, k, v, o, lse, B, H, N, scale, stream);
+    if (D == 128) return causal ? launch_fwd_t<128, true>(q, k, v, o, lse, B, H, Hkv, N, scale, stream)
+                                : launch_fwd_t<128, false>(q, k, v, o, lse, B, H, Hkv, N, scale, stream);
+    return causal ? launch_fwd_t<64, true>(q, k, v, o, lse, B, H, Hkv, N, scale, stream)
+                  : launch_fwd_t<64, false>(q, k, v, o, lse, B, H, Hkv, N, scale, stream);
 }
 
 }  // namespace tk

@@ -31,19 +31,31 @@ size_t delta_bytes(int B, int H, int N)
     return (b + 255) & ~(size_t)255;
 }
 
+int check_heads(int H, int Hkv)
+{
+    return (Hkv >= 1 && Hkv <= H && H % Hkv == 0) ? TK_OK : TK_ERR_BAD_DIM;
+}
+
 }  // namespace
 
 extern "C" {
 
+int tk_attn_fwd_gqa(const void* q, const void* k, const void* v, void* o, float* lse,
+                    int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream)
+{
+    if (!q || !k || !v || !o || !lse) return TK_ERR_NULL_PTR;
+    if (int rc = check_shape(B, Hq, N, D)) return rc;
+    if (int rc = check_heads(Hq, Hkv)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return TK_ERR_MISALIGNED;
+    if (int rc = check_scale(scale)) return rc;
+    hipError_t e = tk::launch_attn_fwd(q, k, v, o, lse, B, Hq, Hkv, N, D, causal != 0, scale, (hipStream_t)stream);
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
 int tk_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                 int B, int H, int N, int D, int causal, float scale, void* stream)
 {
-    if (!q || !k || !v || !o || !lse) return TK_ERR_NULL_PTR;
-    if (int rc = check_shape(B, H, N, D)) return rc;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return TK_ERR_MISALIGNED;
-    if (int rc = check_scale(scale)) return rc;
-    hipError_t e = tk::launch_attn_fwd(q, k, v, o, lse, B, H, N, D, causal != 0, scale, (hipStream_t)stream);
-    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+    return tk_attn_fwd_gqa(q, k, v, o, lse, B, H, H, N, D, causal, scale, stream);
 }
 
 size_t tk_attn_bwd_workspace_bytes(int B, int H, int N, int D)
@@ -61,18 +73,42 @@ int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta, int B, int H
     return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
 }
 
-int tk_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
-                     const float* lse, const float* delta, void* dk, void* dv,
-                     int B, int H, int N, int D, int causal, float scale, void* stream)
+int tk_attn_bwd_dkdv_gqa(const void* q, const void* k, const void* v, const void* d_o,
+                         const float* lse, const float* delta, void* dk, void* dv,
+                         int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream)
 {
     if (!q || !k || !v || !d_o || !lse || !delta || !dk || !dv) return TK_ERR_NULL_PTR;
-    if (int rc = check_shape(B, H, N, D)) return rc;
+    if (int rc = check_shape(B, Hq, N, D)) return rc;
+    if (int rc = check_heads(Hq, Hkv)) return rc;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(lse) ||
         !aligned16(delta) || !aligned16(dk) || !aligned16(dv))
         return TK_ERR_MISALIGNED;
     if (int rc = check_scale(scale)) return rc;
-    hipError_t e = tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, H, N, D, causal != 0, scale,
+    hipError_t e = tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, N, D, causal != 0, scale,
                                             (hipStream_t)stream);
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
+int tk_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
+                     const float* lse, const float* delta, void* dk, void* dv,
+                     int B, int H, int N, int D, int causal, float scale, void* stream)
+{
+    return tk_attn_bwd_dkdv_gqa(q, k, v, d_o, lse, delta, dk, dv, B, H, H, N, D, causal, scale, stream);
+}
+
+int tk_attn_bwd_dq_gqa(const void* q, const void* k, const void* v, const void* d_o,
+                       const float* lse, const float* delta, void* dq,
+                       int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream)
+{
+    if (!q || !k || !v || !d_o || !lse || !delta || !dq) return TK_ERR_NULL_PTR;
+    if (int rc = check_shape(B, Hq, N, D)) return rc;
+    if (int rc = check_heads(Hq, Hkv)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(lse) ||
+        !aligned16(delta) || !aligned16(dq))
+        return TK_ERR_MISALIGNED;
+    if (int rc = check_scale(scale)) return rc;
+    hipError_t e = tk::launch_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, Hq, Hkv, N, D, causal != 0, scale,
+                                          (hipStream_t)stream);
     return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
 }
 
@@ -80,15 +116,34 @@ int tk_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
                    const float* lse, const float* delta, void* dq,
                    int B, int H, int N, int D, int causal, float scale, void* stream)
 {
-    if (!q || !k || !v || !d_o || !lse || !delta || !dq) return TK_ERR_NULL_PTR;
-    if (int rc = check_shape(B, H, N, D)) return rc;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(lse) ||
-        !aligned16(delta) || !aligned16(dq))
+    return tk_attn_bwd_dq_gqa(q, k, v, d_o, lse, delta, dq, B, H, H, N, D, causal, scale, stream);
+}
+
+int tk_attn_bwd_gqa(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse,
+                    void* dq, void* dk, void* dv,
+                    int B, int Hq, int Hkv, int N, int D, int causal, float scale,
+                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return TK_ERR_NULL_PTR;
+    if (int rc = check_shape(B, Hq, N, D)) return rc;
+    if (int rc = check_heads(Hq, Hkv)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(lse) ||
+        !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
         return TK_ERR_MISALIGNED;
     if (int rc = check_scale(scale)) return rc;
-    hipError_t e = tk::launch_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, H, N, D, causal != 0, scale,
-                                          (hipStream_t)stream);
-    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+    if (workspace_bytes < tk_attn_bwd_workspace_bytes(B, Hq, N, D)) return TK_ERR_WORKSPACE_TOO_SMALL;
+
+    hipStream_t s = (hipStream_t)stream;
+    float* delta = (float*)workspace;
+    // 1. Delta = rowsum(dO * O), per query head
+    if (tk::launch_attn_bwd_delta(o, d_o, delta, B, Hq, N, D, s) != hipSuccess) return TK_ERR_LAUNCH;
+    // 2. dK, dV per key tile of every key/value head
+    if (tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, N, D, causal != 0, scale, s) != hipSuccess)
+        return TK_ERR_LAUNCH;
+    // 3. dQ per query tile
+    if (tk::launch_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, Hq, Hkv, N, D, causal != 0, scale, s) != hipSuccess)
+        return TK_ERR_LAUNCH;
+    return TK_OK;
 }
 
 int tk_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse,
@@ -96,25 +151,8 @@ int tk_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
                 int B, int H, int N, int D, int causal, float scale,
                 void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return TK_ERR_NULL_PTR;
-    if (int rc = check_shape(B, H, N, D)) return rc;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(lse) ||
-        !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
-        return TK_ERR_MISALIGNED;
-    if (int rc = check_scale(scale)) return rc;
-    if (workspace_bytes < tk_attn_bwd_workspace_bytes(B, H, N, D)) return TK_ERR_WORKSPACE_TOO_SMALL;
-
-    hipStream_t s = (hipStream_t)stream;
-    float* delta = (float*)workspace;
-    // 1. Delta = rowsum(dO * O)
-    if (tk::launch_attn_bwd_delta(o, d_o, delta, B, H, N, D, s) != hipSuccess) return TK_ERR_LAUNCH;
-    // 2. dK, dV per key tile
-    if (tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, H, N, D, causal != 0, scale, s) != hipSuccess)
-        return TK_ERR_LAUNCH;
-    // 3. dQ per query tile
-    if (tk::launch_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, H, N, D, causal != 0, scale, s) != hipSuccess)
-        return TK_ERR_LAUNCH;
-    return TK_OK;
+    return tk_attn_bwd_gqa(q, k, v, o, d_o, lse, dq, dk, dv, B, H, H, N, D, causal, scale,
+                           workspace, workspace_bytes, stream);
 }
 
 int tk_mfma_probe(const void* operands, float* sink, int workgroups, int iters, void* stream)

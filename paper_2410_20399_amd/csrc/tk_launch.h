@@ -13,8 +13,10 @@ inline hipError_t compute_unit_count(int* cus) {
     return hipDeviceGetAttribute(cus, hipDeviceAttributeMultiprocessorCount, dev);
 }
 
+// H query heads share Hkv key/value heads in groups of H / Hkv consecutive heads (Hkv == H: plain
+// multi-head attention).  q, o, d_o, dq: [B,H,N,D]; k, v, dk, dv: [B,Hkv,N,D]; lse, delta: [B,H,N].
 hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
-                           int B, int H, int N, int D, int causal, float scale, hipStream_t stream);
+                           int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream);
 
 // Delta_i = sum_d dO_id O_id
 hipError_t launch_attn_bwd_delta(const void* o, const void* d_o, float* delta,
@@ -23,12 +25,12 @@ hipError_t launch_attn_bwd_delta(const void* o, const void* d_o, float* delta,
 // dK, dV (key-tile parallel)
 hipError_t launch_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
                                 const float* lse, const float* delta, void* dk, void* dv,
-                                int B, int H, int N, int D, int causal, float scale, hipStream_t stream);
+                                int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream);
 
 // dQ (query-tile parallel)
 hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
                               const float* lse, const float* delta, void* dq,
-                              int B, int H, int N, int D, int causal, float scale, hipStream_t stream);
+                              int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream);
 
 // bare MFMA stream (measurement aid): 32 MFMAs per wave per iteration
 hipError_t launch_mfma_probe(const void* operands, float* sink, int workgroups, int iters, hipStream_t stream);

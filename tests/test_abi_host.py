@@ -125,6 +125,25 @@ def test_stage_entries_reject_bad_arguments(lib):
         assert fn(*([P] * nptr), 1, 1, 128, 96, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
 
 
+def test_gqa_entries_reject_bad_arguments(lib):
+    from paper_2410_20399_amd import attn as a
+    f = ctypes.c_float
+    sz = ctypes.c_size_t
+    # head counts: Hkv must be >= 1, <= Hq and divide Hq
+    for hq, hkv in ((4, 0), (4, 3), (4, 8), (4, -1)):
+        assert lib.tk_attn_fwd_gqa(P, P, P, P, P, 1, hq, hkv, 128, 64, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
+        assert lib.tk_attn_bwd_gqa(P, P, P, P, P, P, P, P, P, 1, hq, hkv, 128, 64, 0, f(0.125), P, sz(1 << 30), None) == a.TK_ERR_BAD_DIM
+        assert lib.tk_attn_bwd_dkdv_gqa(P, P, P, P, P, P, P, P, 1, hq, hkv, 128, 64, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
+        assert lib.tk_attn_bwd_dq_gqa(P, P, P, P, P, P, P, 1, hq, hkv, 128, 64, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
+    assert lib.tk_attn_fwd_gqa(None, P, P, P, P, 1, 4, 2, 128, 64, 0, f(0.125), None) == a.TK_ERR_NULL_PTR
+    assert lib.tk_attn_fwd_gqa(P, ODD, P, P, P, 1, 4, 2, 128, 64, 0, f(0.125), None) == a.TK_ERR_MISALIGNED
+    assert lib.tk_attn_fwd_gqa(P, P, P, P, P, 1, 4, 2, 100, 64, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
+    assert lib.tk_attn_fwd_gqa(P, P, P, P, P, 1, 4, 2, 128, 64, 0, f(-1.0), None) == a.TK_ERR_BAD_SCALE
+    need = lib.tk_attn_bwd_workspace_bytes(1, 4, 128, 64)
+    assert lib.tk_attn_bwd_gqa(P, P, P, P, P, P, P, P, P, 1, 4, 2, 128, 64, 0, f(0.125), P, sz(need - 1), None) == a.TK_ERR_WORKSPACE_TOO_SMALL
+    assert lib.tk_attn_bwd_gqa(P, P, P, P, P, P, P, P, None, 1, 4, 2, 128, 64, 0, f(0.125), P, sz(need), None) == a.TK_ERR_NULL_PTR
+
+
 def test_mfma_probe_rejects_bad_arguments(lib):
     from paper_2410_20399_amd import attn as a
     assert lib.tk_mfma_probe(None, P, 1, 1, None) == a.TK_ERR_NULL_PTR
