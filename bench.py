@@ -55,22 +55,36 @@ def main():
     q, k, v, d_o = workloads.make_inputs(w, need_do=True)
     qd, kd, vd, dod = (t.to(dev) for t in (q, k, v, d_o))
     B, H, N, D = w.B, w.H, w.N, w.D
+    Hkv = w.kv_heads                          # == H unless the workload is grouped-query
     o = torch.empty_like(qd)
     lse = torch.empty((B, H, N), dtype=torch.float32, device=dev)
-    dq, dk, dv = torch.empty_like(qd), torch.empty_like(qd), torch.empty_like(qd)
+    dq, dk, dv = torch.empty_like(qd), torch.empty_like(kd), torch.empty_like(vd)
     ws = attn.alloc_bwd_workspace(B, H, N, D, dev)
     ws_bytes = ws.numel()
+    delta = ws[:B * H * N * 4].view(torch.float32)      # the workspace is exactly the Delta array
     stream = torch.cuda.current_stream()
 
     def check(rc, what):
         if rc != attn.TK_OK:
             raise attn.TkAttnError(rc, what)
 
+    # multi-head workloads go through tk_attn_fwd / tk_attn_bwd and their stage entry points,
+    # grouped-query ones through the *_gqa entry points (the same kernels)
+    if Hkv == H:
+        fwd_call = lambda: attn.tk_attn_fwd(qd, kd, vd, o, lse, B, H, N, D, w.causal, w.scale, stream)
+        bwd_call = lambda: attn.tk_attn_bwd(qd, kd, vd, o, dod, lse, dq, dk, dv, B, H, N, D, w.causal, w.scale, ws, ws_bytes, stream)
+        dkdv_call = lambda: attn.tk_attn_bwd_dkdv(qd, kd, vd, dod, lse, delta, dk, dv, B, H, N, D, w.causal, w.scale, stream)
+        dq_call = lambda: attn.tk_attn_bwd_dq(qd, kd, vd, dod, lse, delta, dq, B, H, N, D, w.causal, w.scale, stream)
+    else:
+        fwd_call = lambda: attn.tk_attn_fwd_gqa(qd, kd, vd, o, lse, B, H, Hkv, N, D, w.causal, w.scale, stream)
+        bwd_call = lambda: attn.tk_attn_bwd_gqa(qd, kd, vd, o, dod, lse, dq, dk, dv, B, H, Hkv, N, D, w.causal, w.scale, ws, ws_bytes, stream)
+        dkdv_call = lambda: attn.tk_attn_bwd_dkdv_gqa(qd, kd, vd, dod, lse, delta, dk, dv, B, H, Hkv, N, D, w.causal, w.scale, stream)
+        dq_call = lambda: attn.tk_attn_bwd_dq_gqa(qd, kd, vd, dod, lse, delta, dq, B, H, Hkv, N, D, w.causal, w.scale, stream)
+
     def step():
-        check(attn.tk_attn_fwd(qd, kd, vd, o, lse, B, H, N, D, w.causal, w.scale, stream), "tk_attn_fwd")
+        check(fwd_call(), "tk_attn_fwd")
         if w.backward:
-            check(attn.tk_attn_bwd(qd, kd, vd, o, dod, lse, dq, dk, dv, B, H, N, D, w.causal, w.scale,
-                                   ws, ws_bytes, stream), "tk_attn_bwd")
+            check(bwd_call(), "tk_attn_bwd")
 
     for _ in range(args.warmup):
         step()
@@ -87,14 +101,13 @@ def main():
     value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
 
     # ---- per-kernel durations: the same kernels through the stage entry points, HIP events on the launch stream
-    delta = ws[:B * H * N * 4].view(torch.float32)
 
-    stages = [("attn_fwd_kernel", lambda: check(attn.tk_attn_fwd(qd, kd, vd, o, lse, B, H, N, D, w.causal, w.scale, stream), "fwd"))]
+    stages = [("attn_fwd_kernel", lambda: check(fwd_call(), "fwd"))]
     if w.backward:
         stages += [
             ("attn_bwd_delta_kernel", lambda: check(attn.tk_attn_bwd_delta(o, dod, delta, B, H, N, D, stream), "delta")),
-            ("attn_bwd_dkdv_kernel", lambda: check(attn.tk_attn_bwd_dkdv(qd, kd, vd, dod, lse, delta, dk, dv, B, H, N, D, w.causal, w.scale, stream), "dkdv")),
-            ("attn_bwd_dq_kernel", lambda: check(attn.tk_attn_bwd_dq(qd, kd, vd, dod, lse, delta, dq, B, H, N, D, w.causal, w.scale, stream), "dq")),
+            ("attn_bwd_dkdv_kernel", lambda: check(dkdv_call(), "dkdv")),
+            ("attn_bwd_dq_kernel", lambda: check(dq_call(), "dq")),
         ]
     kernel_ms = {name: 0.0 for name, _ in stages}
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)] for _ in range(args.steps)]
@@ -114,7 +127,7 @@ def main():
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "B": B, "H": H, "N": N, "D": D, "causal": w.causal,
+        "config": {"workload": w.name, "B": B, "H": H, "Hkv": Hkv, "N": N, "D": D, "causal": w.causal,
                    "pass": "fwd+bwd" if w.backward else "fwd",
                    "flop_convention": "fwd 4*B*H*N^2*D, bwd 2.5x fwd, halved when causal"},
         "frac_of_mfma_peak": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
@@ -185,25 +198,36 @@ def main():
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
     if not args.no_cpu_baseline:
         from oracle import attn_oracle as orc
+        # one sample = one key/value head with the query heads of its group (one head when multi-head)
+        G = H // Hkv
         heads, spent, cpu_flops = [], 0.0, 0.0
-        per_head = (flops_fwd + flops_bwd) / (B * H)
-        n_max = min(64, B * H)
+        per_group = (flops_fwd + flops_bwd) / (B * Hkv)
+        n_max = min(64, B * Hkv)
         for idx in range(n_max):
-            b, h = divmod(idx * (B * H // n_max), H)
-            a = [t[b, h].double().numpy() for t in ((q, k, v, d_o) if w.backward else (q, k, v))]
+            b, hk = divmod(idx * (B * Hkv // n_max), Hkv)
+            qs = q[b:b + 1, hk * G:(hk + 1) * G].double().numpy()
+            ks, vs = k[b:b + 1, hk:hk + 1].double().numpy(), v[b:b + 1, hk:hk + 1].double().numpy()
             c0 = time.perf_counter()
-            orc.attn_fwd(a[0], a[1], a[2], w.causal, w.scale)
+            if G == 1:
+                orc.attn_fwd(qs, ks, vs, w.causal, w.scale)
+            else:
+                orc.gqa_fwd(qs, ks, vs, w.causal, w.scale)
             if w.backward:
-                orc.attn_bwd(a[0], a[1], a[2], a[3], w.causal, w.scale)
+                dos = d_o[b:b + 1, hk * G:(hk + 1) * G].double().numpy()
+                if G == 1:
+                    orc.attn_bwd(qs, ks, vs, dos, w.causal, w.scale)
+                else:
+                    orc.gqa_bwd(qs, ks, vs, dos, w.causal, w.scale)
             spent += time.perf_counter() - c0
-            cpu_flops += per_head
-            heads.append([b, h])
+            cpu_flops += per_group
+            heads.append([b, hk])
             if spent >= args.cpu_seconds:
                 break
         out["cpu_baseline"] = {"value": round(cpu_flops / spent / 1e12, 6), "unit": "TFLOP/s",
                                "cores": orc.num_threads(), "kind": "oracle",
-                               "sample": f"fp64 oracle fwd{'+bwd' if w.backward else ''} on {len(heads)} of {B * H} heads "
-                                         f"(b,h)={heads[0]}..{heads[-1]} in steps of {B * H // n_max} flat heads, {spent:.1f} s, same FLOP convention"}
+                               "sample": f"fp64 oracle fwd{'+bwd' if w.backward else ''} on {len(heads)} of {B * Hkv} "
+                                         f"{'heads' if G == 1 else f'key/value heads (each with its {G} query heads)'} "
+                                         f"(b,h)={heads[0]}..{heads[-1]} in steps of {B * Hkv // n_max} flat heads, {spent:.1f} s, same FLOP convention"}
     print(json.dumps(out))
 
 

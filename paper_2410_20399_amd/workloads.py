@@ -3,7 +3,7 @@
 Both the HIP path's tests/benchmark and the CPU oracle's tests draw their
 inputs here, so the two sides see the same bf16 bit patterns.  The recipe:
 one CPU ``torch.Generator`` seeded with ``20399 + index``; Q, K, V, dO drawn in
-that order as float32 standard normals of shape [B, H, N, D] and rounded to
+that order as float32 standard normals of shape [B, H, N, D] (K, V: [B, Hkv, N, D]) and rounded to
 bf16 (round-to-nearest-even); for workloads with ``q_mul`` the rounded Q is
 multiplied by that power of two (exact in bf16).
 """
@@ -24,6 +24,11 @@ class Workload:
     causal: bool
     backward: bool
     q_mul: float = 1.0
+    Hkv: int = 0          # key/value heads (grouped-query attention); 0 = H, plain multi-head
+
+    @property
+    def kv_heads(self) -> int:
+        return self.Hkv or self.H
 
     @property
     def scale(self) -> float:
@@ -52,18 +57,21 @@ WORKLOADS = {
     5: Workload(5, "fwdbwd_causal_b1_h16_n16384_d128", 1, 16, 16384, 128, True, True),
     6: Workload(6, "fwdbwd_causal_b16_h16_n4096_d128", 16, 16, 4096, 128, True, True),
     7: Workload(7, "fwdbwd_nc_b16_h16_n4096_d128", 16, 16, 4096, 128, False, True),
+    # grouped-query variant of the target shape: same query-side work, 4 query heads per key/value head
+    8: Workload(8, "fwdbwd_causal_gqa_b8_hq32_hkv8_n4096_d128", 8, 32, 4096, 128, True, True, 1.0, 8),
 }
 
 
 def make_inputs(w: Workload, need_do: bool = None):
-    """Return (q, k, v, d_o) CPU bf16 tensors [B, H, N, D]; d_o is None unless asked for."""
+    """Return (q, k, v, d_o) CPU bf16 tensors [B, H, N, D] (k, v: [B, Hkv, N, D]); d_o is None unless asked for."""
     if need_do is None:
         need_do = w.backward
     g = torch.Generator().manual_seed(w.seed)
     shape = (w.B, w.H, w.N, w.D)
+    kv_shape = (w.B, w.kv_heads, w.N, w.D)
     q = torch.randn(shape, generator=g, dtype=torch.float32).to(torch.bfloat16)
-    k = torch.randn(shape, generator=g, dtype=torch.float32).to(torch.bfloat16)
-    v = torch.randn(shape, generator=g, dtype=torch.float32).to(torch.bfloat16)
+    k = torch.randn(kv_shape, generator=g, dtype=torch.float32).to(torch.bfloat16)
+    v = torch.randn(kv_shape, generator=g, dtype=torch.float32).to(torch.bfloat16)
     d_o = torch.randn(shape, generator=g, dtype=torch.float32).to(torch.bfloat16) if need_do else None
     if w.q_mul != 1.0:
         q = q * w.q_mul
