@@ -4,7 +4,7 @@
 // here is the chain rule with P recomputed from the saved log-sum-exp:
 //
 //   kernel 1  Delta_i = sum_d dO_id O_id          (HBM stream)
-//   kernel 2  dK, dV: one workgroup per 128-key tile, wave w owns keys 32w..32w+31 and keeps
+//   kernel 2  dK, dV: persistent workgroups walk the 128-key tiles; wave w owns keys 32w..32w+31 and keeps
 //             their dK^T, dV^T accumulators in registers while it loops over 32-query blocks:
 //               S  = Q_i K_j^T            P  = 2^(S*c - LSE_i*log2e)
 //               dP = dO_i V_j^T           dS = P (dP - Delta_i)
