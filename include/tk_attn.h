@@ -13,8 +13,8 @@
  *   - Every tensor pointer is a DEVICE pointer owned by the caller, to
  *     contiguous row-major memory, 16-byte aligned.  Q, K, V, O, dO, dQ, dK,
  *     dV are bf16 [B, H, N, D]; LSE is fp32 [B, H, N].
- *   - D is 64 or 128.  N is a positive multiple of 128.  B, H >= 1 and
- *     B*H*ceil(N/128) must fit a 31-bit grid.
+ *   - D is 64 or 128.  B, H, N >= 1 (any sequence length: the kernels work on
+ *     tiles of 128 rows and mask the tail) and B*H*ceil(N/128) must fit a 31-bit grid.
  *   - scale must be finite and > 0 (the running maximum is taken on raw
  *     scores, which is only the maximum of the scaled scores for scale > 0).
  *   - causal != 0 masks keys j > i (the diagonal is kept).
@@ -38,7 +38,7 @@ extern "C" {
 enum {
     TK_OK = 0,
     TK_ERR_NULL_PTR = -1,            /* a required pointer is NULL */
-    TK_ERR_BAD_DIM = -2,             /* D not in {64,128}, N not a positive multiple of 128, B or H < 1, grid overflow */
+    TK_ERR_BAD_DIM = -2,             /* D not in {64,128}; B, H or N < 1; Hkv not dividing Hq; grid overflow */
     TK_ERR_MISALIGNED = -3,          /* a tensor pointer is not 16-byte aligned */
     TK_ERR_BAD_SCALE = -4,           /* scale is not finite or not > 0 */
     TK_ERR_WORKSPACE_TOO_SMALL = -5, /* workspace_bytes < tk_attn_bwd_workspace_bytes(...) */

@@ -40,7 +40,7 @@ void attn_bwd_delta_kernel(const bf16* __restrict__ O, const bf16* __restrict__ 
 {
     constexpr int kLanesPerRow = D / 8;
     const size_t chunk = (size_t)blockIdx.x * 256 + threadIdx.x;   // one 8-element chunk per thread
-    if (chunk >= n_chunks) return;                                  // n_chunks is a multiple of 256: never taken
+    if (chunk >= n_chunks) return;                                  // (whole rows: n_chunks is a multiple of D/8)
     bf16x8 a = *(const bf16x8*)(O + chunk * 8);
     bf16x8 b = *(const bf16x8*)(dO + chunk * 8);
     float acc = 0.f;
@@ -54,8 +54,8 @@ void attn_bwd_delta_kernel(const bf16* __restrict__ O, const bf16* __restrict__ 
 hipError_t launch_attn_bwd_delta(const void* o, const void* d_o, float* delta,
                                  int B, int H, int N, int D, hipStream_t stream)
 {
-    const size_t n_chunks = (size_t)B * H * N * D / 8;   // N % 128 == 0, so a multiple of 256
-    const dim3 grid((unsigned)(n_chunks / 256));
+    const size_t n_chunks = (size_t)B * H * N * D / 8;
+    const dim3 grid((unsigned)((n_chunks + 255) / 256));
     if (D == 128) hipLaunchKernelGGL((attn_bwd_delta_kernel<128>), grid, dim3(256), 0, stream, (const bf16*)o, (const bf16*)d_o, delta, n_chunks);
     else          hipLaunchKernelGGL((attn_bwd_delta_kernel<64>), grid, dim3(256), 0, stream, (const bf16*)o, (const bf16*)d_o, delta, n_chunks);
     return hipGetLastError();
@@ -64,6 +64,9 @@ hipError_t launch_attn_bwd_delta(const void* o, const void* d_o, float* delta,
 // ------------------------------------------------------------------------------------------
 // kernel 2: dK, dV
 // ------------------------------------------------------------------------------------------
+// LSE stand-in for query rows past the end of a sequence: P = 2^(s - inf) = 0 for them.
+__device__ float g_lse_pad[1] = {INFINITY};
+
 template <int D>
 struct DkdvShape {
     static constexpr int kWaves = 4;
@@ -107,7 +110,8 @@ template <int D> __device__ __forceinline__ int swz(int row) {
 // the query-block stream never stops: the loads issued during the last blocks of one key tile
 // already fetch the first blocks of the next, and the next tile's K, V fragments are requested
 // before the current tile's results are stored.
-template <int D, bool CAUSAL>
+// TAIL: N is not a multiple of 128 (the aligned case compiles without any of the tail code).
+template <int D, bool CAUSAL, bool TAIL>
 __global__ __launch_bounds__(256, 1)
 void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                           const bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
@@ -164,33 +168,64 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     }
     // Producer side of the ring: a cursor over the query blocks of this workgroup's passes, in the
     // order the passes consume them.  Every call issues the same number of loads (the vmcnt waits
-    // below count them); once the walk is exhausted it fetches `spare_row`'s block again into a
+    // below count them); once the walk is exhausted it fetches the spare block again into a
     // stage nobody reads.
-    int p_vu = blockIdx.x, p_half = 0, p_blk = 0, p_nblocks = 0, p_g = 0;
-    size_t p_row0 = 0;                      // first streamed row (of the group's first query head) of the producer's pass
-    size_t spare_row = 0;
+    // N need not be a multiple of the tile sizes: the kernel works on the sequence padded to 128
+    // (n_pad).  Reads of rows >= N are redirected to row N-1; a query row >= N gets LSE = +inf, so
+    // its P and dS are exactly 0; key rows >= N are computed like any other and not stored.
+    const int n_pad = num_kv_tiles * S::kTileKV;
+    int p_vu = blockIdx.x, p_half = 0, p_blk = 0, p_nblocks = 0, p_g = 0, p_ibegin = 0;
+    size_t p_head_row = 0;                  // first row of the group's first query head of the producer's pass
+    size_t spare_head_row = 0;
+    int spare_i0 = 0;
     int p_count = 0;                        // blocks issued so far (selects the ring stage)
     auto producer_open = [&]() {            // set the cursor to the first block of pass (p_vu, p_half)
         int bh, kt;
         pass_tile(p_vu, p_half, bh, kt);
-        const int i_begin = CAUSAL ? kt * S::kTileKV : 0;
-        p_row0 = q_head_row(bh) + i_begin;
-        p_nblocks = (N - i_begin) / S::kTileQ;
+        p_ibegin = CAUSAL ? kt * S::kTileKV : 0;
+        p_head_row = q_head_row(bh);
+        p_nblocks = (n_pad - p_ibegin) / S::kTileQ;
         p_blk = 0;
         p_g = 0;
     };
     auto issue_next = [&]() {
         const bool live = p_vu < total_units;
-        const size_t row = live ? p_row0 + (size_t)p_g * N + (size_t)p_blk * S::kTileQ : spare_row;
+        const size_t head_row = live ? p_head_row + (size_t)p_g * N : spare_head_row;
+        const int i0 = live ? p_ibegin + p_blk * S::kTileQ : spare_i0;      // first query of the block, within its head
+        const size_t row = head_row + i0;
         char* base = ring + (p_count & (S::kStages - 1)) * S::kStageBytes;
+        if (!TAIL || i0 + S::kTileQ <= N) {
 #pragma unroll
-        for (int it = 0; it < S::kQLoads; it++)
-            load_global_to_lds16_untracked(Q + row * D + q_src[it], base + it * (S::kThreads * 16) + wave * 1024);
+            for (int it = 0; it < S::kQLoads; it++)
+                load_global_to_lds16_untracked(Q + row * D + q_src[it], base + it * (S::kThreads * 16) + wave * 1024);
 #pragma unroll
-        for (int it = 0; it < S::kQLoads; it++)
-            load_global_to_lds16_untracked(dO + row * D + q_src[it],
-                                           base + S::kQTileBytes + it * (S::kThreads * 16) + wave * 1024);
-        if (wave == 0 && lane < 16) {   // 8 lanes fetch LSE[row..row+31], 8 lanes Delta[row..row+31]
+            for (int it = 0; it < S::kQLoads; it++)
+                load_global_to_lds16_untracked(dO + row * D + q_src[it],
+                                               base + S::kQTileBytes + it * (S::kThreads * 16) + wave * 1024);
+        } else {
+            // the block runs past the last query: rows >= N fetch row N-1 instead
+#pragma unroll
+            for (int it = 0; it < S::kQLoads; it++) {
+                const int r = i0 + (it * S::kThreads + tid) / S::kChunksPerRow;
+                const int back = (r < N ? 0 : r - (N - 1)) * D;         // elements to step back
+                load_global_to_lds16_untracked(Q + row * D + q_src[it] - back, base + it * (S::kThreads * 16) + wave * 1024);
+            }
+#pragma unroll
+            for (int it = 0; it < S::kQLoads; it++) {
+                const int r = i0 + (it * S::kThreads + tid) / S::kChunksPerRow;
+                const int back = (r < N ? 0 : r - (N - 1)) * D;
+                load_global_to_lds16_untracked(dO + row * D + q_src[it] - back,
+                                               base + S::kQTileBytes + it * (S::kThreads * 16) + wave * 1024);
+            }
+        }
+        if (TAIL) {
+            if (wave == 0) {   // lanes 0..31 fetch LSE of the block's 32 queries, lanes 32..63 their Delta
+                const int r = i0 + l32;
+                const float* src = (lane < 32) ? (r < N ? LSE + head_row + r : g_lse_pad)
+                                               : Delta + head_row + (r < N ? r : N - 1);
+                load_global_to_lds4_untracked(src, base + 2 * S::kQTileBytes);
+            }
+        } else if (wave == 0 && lane < 16) {   // 8 lanes fetch LSE[row..row+31], 8 lanes Delta[row..row+31], 16 bytes each
             const float* src = (lane < 8) ? (LSE + row + lane * 4) : (Delta + row + (lane - 8) * 4);
             load_global_to_lds16_untracked(src, base + 2 * S::kQTileBytes);
         }
@@ -214,7 +249,8 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     constexpr int kSteps = D / 16;          // MFMA steps of S / dP; also 2 * (D/32) steps of dV^T / dK^T
     bf16x8 kf[D / 16], vf[D / 16];          // K, V fragments of this wave's 32 keys (B operands of S = Q K^T and dP = dO V^T)
     auto load_kv = [&](int bh, int kt) {
-        const size_t row = (size_t)bh * N + kt * S::kTileKV + wave * 32 + l32;
+        const int key = kt * S::kTileKV + wave * 32 + l32;
+        const size_t row = (size_t)bh * N + ((!TAIL || key < N) ? key : N - 1);
 #pragma unroll
         for (int kb = 0; kb < D / 16; kb++) {
             kf[kb] = *(const bf16x8*)(K + row * D + kb * 16 + h * 8);
@@ -228,7 +264,8 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         int bh, kt;
         pass_tile(c_vu, c_half, bh, kt);
         producer_open();
-        spare_row = p_row0;
+        spare_head_row = p_head_row;
+        spare_i0 = p_ibegin;
 #pragma unroll
         for (int b = 0; b < S::kAhead; b++) issue_next();
         load_kv(bh, kt);
@@ -243,8 +280,9 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     const int jw0 = j0 + wave * 32;                // first key of this wave
     const int my_j = jw0 + l32;
     const int i_begin = CAUSAL ? j0 : 0;
-    const int n_blocks = (N - i_begin) / S::kTileQ;   // per query head of the group
-    spare_row = q_head_row(bh) + i_begin;
+    const int n_blocks = (n_pad - i_begin) / S::kTileQ;   // per query head of the group
+    spare_head_row = q_head_row(bh);
+    spare_i0 = i_begin;
 
     f32x16 dk_acc[D / 32], dv_acc[D / 32];
 #pragma unroll
@@ -430,7 +468,7 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
             const int row = i * kRowsPerStore + sub_row;
             const char* src = my_epi + row * S::kEpiPitch + col16 * 16;
             const bf16x4 lo = *(const bf16x4*)src, hi = *(const bf16x4*)(src + 8);
-            *(bf16x8*)(dst + (size_t)row * D + col16 * 8) = concat(lo, hi);
+            if (!TAIL || jw0 + row < N) *(bf16x8*)(dst + (size_t)row * D + col16 * 8) = concat(lo, hi);
         }
     };
     store_tile(dk_acc, scale, dK + head + (size_t)jw0 * D);
@@ -439,22 +477,32 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     wait_vmcnt<0>();      // the spare prefetches of the last blocks must not outlive the workgroup's LDS
 }
 
+template <int D, bool CAUSAL, bool TAIL>
+static hipError_t launch_dkdv_tt(const void* q, const void* k, const void* v, const void* d_o,
+                                 const float* lse, const float* delta, void* dk, void* dv,
+                                 int B, int H, int Hkv, int N, float scale, hipStream_t stream)
+{
+    using S = DkdvShape<D>;
+    const int num_kv_tiles = (N + S::kTileKV - 1) / S::kTileKV;
+    const int total_units = B * Hkv * (CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles);
+    int cus = 0;
+    hipError_t e = compute_unit_count(&cus);
+    if (e != hipSuccess) return e;
+    const int grid = total_units < cus ? total_units : cus;     // one resident workgroup per compute unit
+    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL, TAIL>), dim3(grid), dim3(S::kThreads), 0, stream,
+                       (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
+                       (bf16*)dk, (bf16*)dv, N, num_kv_tiles, total_units, scale, H, Hkv);
+    return hipGetLastError();
+}
+
 template <int D, bool CAUSAL>
 static hipError_t launch_dkdv_t(const void* q, const void* k, const void* v, const void* d_o,
                                 const float* lse, const float* delta, void* dk, void* dv,
                                 int B, int H, int Hkv, int N, float scale, hipStream_t stream)
 {
     using S = DkdvShape<D>;
-    const int num_kv_tiles = N / S::kTileKV;
-    const int total_units = B * Hkv * (CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles);
-    int cus = 0;
-    hipError_t e = compute_unit_count(&cus);
-    if (e != hipSuccess) return e;
-    const int grid = total_units < cus ? total_units : cus;     // one resident workgroup per compute unit
-    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL>), dim3(grid), dim3(S::kThreads), 0, stream,
-                       (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
-                       (bf16*)dk, (bf16*)dv, N, num_kv_tiles, total_units, scale, H, Hkv);
-    return hipGetLastError();
+    return N % S::kTileKV ? launch_dkdv_tt<D, CAUSAL, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, N, scale, stream)
+                          : launch_dkdv_tt<D, CAUSAL, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, N, scale, stream);
 }
 
 hipError_t launch_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
@@ -483,7 +531,7 @@ struct DqShape {
     static constexpr int kLoadsPerTile = kTileKV * kChunksPerRow / kThreads;   // per thread, per tensor
 };
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool TAIL>
 __global__ __launch_bounds__(256, 2)
 void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                         const bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
@@ -516,17 +564,20 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
     if (pass == 1 && qt == num_q_tiles - 1 - unit) break;   // odd tile count: the middle tile has no partner
     const int q0 = qt * S::kTileQ + wave * 32;
     const int my_q = q0 + l32;
+    // N need not be a multiple of the tile sizes: the kernel works on the sequence padded to 128,
+    // reads of rows >= N are redirected to row N-1, keys >= N are masked, rows >= N are not stored.
+    const int my_q_ld = (!TAIL || my_q < N) ? my_q : N - 1;
     const float c = scale * kLog2e;
 
     // ---- Q_i, dO_i fragments (B operands of S^T = K Q^T and dP^T = V dO^T) and the row statistics
     bf16x8 qf[D / 16], dof[D / 16];
 #pragma unroll
     for (int kb = 0; kb < D / 16; kb++) {
-        qf[kb] = *(const bf16x8*)(Q + head + (size_t)my_q * D + kb * 16 + h * 8);
-        dof[kb] = *(const bf16x8*)(dO + head + (size_t)my_q * D + kb * 16 + h * 8);
+        qf[kb] = *(const bf16x8*)(Q + head + (size_t)my_q_ld * D + kb * 16 + h * 8);
+        dof[kb] = *(const bf16x8*)(dO + head + (size_t)my_q_ld * D + kb * 16 + h * 8);
     }
-    const float lse2 = LSE[(size_t)bh * N + my_q] * kLog2e;
-    const float delta = Delta[(size_t)bh * N + my_q];
+    const float lse2 = LSE[(size_t)bh * N + my_q_ld] * kLog2e;
+    const float delta = Delta[(size_t)bh * N + my_q_ld];
 
     // ---- direct-to-LDS tile loads (same slot arithmetic as the forward kernel)
     int kv_src[S::kLoadsPerTile];
@@ -537,14 +588,26 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
         kv_src[it] = row * D + ((pc ^ swz<D>(row)) * 8);
     }
     auto issue_tile = [&](char* base, int tile) {
-        const bf16* kt = Kh + (size_t)tile * S::kTileKV * D;
-        const bf16* vt = Vh + (size_t)tile * S::kTileKV * D;
+        const int j0 = tile * S::kTileKV;
+        const bf16* kt = Kh + (size_t)j0 * D;
+        const bf16* vt = Vh + (size_t)j0 * D;
+        if (!TAIL || j0 + S::kTileKV <= N) {
 #pragma unroll
-        for (int it = 0; it < S::kLoadsPerTile; it++)
-            load_global_to_lds16(kt + kv_src[it], base + wave * 1024 + it * (S::kThreads * 16));
+            for (int it = 0; it < S::kLoadsPerTile; it++)
+                load_global_to_lds16(kt + kv_src[it], base + wave * 1024 + it * (S::kThreads * 16));
 #pragma unroll
-        for (int it = 0; it < S::kLoadsPerTile; it++)
-            load_global_to_lds16(vt + kv_src[it], base + S::kTileBytes + wave * 1024 + it * (S::kThreads * 16));
+            for (int it = 0; it < S::kLoadsPerTile; it++)
+                load_global_to_lds16(vt + kv_src[it], base + S::kTileBytes + wave * 1024 + it * (S::kThreads * 16));
+        } else {
+            // the tile runs past the last key: rows >= N fetch row N-1 instead (they are masked later)
+#pragma unroll
+            for (int it = 0; it < S::kLoadsPerTile; it++) {
+                const int row = j0 + (it * S::kThreads + tid) / S::kChunksPerRow;
+                const int back = (row < N ? 0 : row - (N - 1)) * D;     // elements to step back
+                load_global_to_lds16(kt + kv_src[it] - back, base + wave * 1024 + it * (S::kThreads * 16));
+                load_global_to_lds16(vt + kv_src[it] - back, base + S::kTileBytes + wave * 1024 + it * (S::kThreads * 16));
+            }
+        }
         __builtin_amdgcn_sched_barrier(0);
     };
 
@@ -566,7 +629,8 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
         const int j0 = tile * S::kTileKV;
         if (CAUSAL && j0 > q0 + 31) return;          // every key of the tile is masked for this wave
         const char* vs = ks + S::kTileBytes;
-        const bool diag = CAUSAL && (j0 + S::kTileKV - 1 > q0);   // the tile crosses this wave's diagonal
+        // the tile crosses this wave's diagonal, or runs past the last key
+        const bool diag = (CAUSAL && (j0 + S::kTileKV - 1 > q0)) || (TAIL && j0 + S::kTileKV > N);
         // The tile is processed in two halves of 32 keys, so that only one half's S^T / dP^T
         // accumulators are live at a time.
 #pragma unroll
@@ -585,8 +649,10 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
             // branch of its own (P = 2^-inf = 0), so the common case carries no compare / select.
             if (diag) {
 #pragma unroll
-                for (int r = 0; r < 16; r++)
-                    if (j0 + 32 * b + 8 * (r >> 2) + 4 * h + (r & 3) > my_q) s[r] = -INFINITY;
+                for (int r = 0; r < 16; r++) {
+                    const int key = j0 + 32 * b + 8 * (r >> 2) + 4 * h + (r & 3);
+                    if ((CAUSAL && key > my_q) || (TAIL && key >= N)) s[r] = -INFINITY;
+                }
             }
 #pragma unroll
             for (int r = 0; r < 16; r++) {
@@ -611,7 +677,8 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
         }
     };
 
-    const int n_tiles = CAUSAL ? (qt * S::kTileQ + S::kTileQ) / S::kTileKV : N / S::kTileKV;   // even
+    // key tiles of the sequence padded to the query tile size; even
+    const int n_tiles = (CAUSAL ? qt * S::kTileQ + S::kTileQ : num_q_tiles * S::kTileQ) / S::kTileKV;
     issue_tile(stage0, 0);
     wait_vmcnt<0>();
     __syncthreads();
@@ -627,16 +694,32 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
     }
 
     // ---- epilogue: dQ = scale * acc; lane <-> query, register r of block db <-> column 32db + 8*(r/4) + 4h + r%4
-    bf16* dQr = dQ + head + (size_t)my_q * D;
+    if (!TAIL || my_q < N) {
+        bf16* dQr = dQ + head + (size_t)my_q * D;
 #pragma unroll
-    for (int db = 0; db < D / 32; db++)
+        for (int db = 0; db < D / 32; db++)
 #pragma unroll
-        for (int g = 0; g < 4; g++) {
-            bf16x2 lo = cvt2(dq_acc[db][4 * g + 0] * scale, dq_acc[db][4 * g + 1] * scale);
-            bf16x2 hi = cvt2(dq_acc[db][4 * g + 2] * scale, dq_acc[db][4 * g + 3] * scale);
-            *(bf16x4*)(dQr + 32 * db + 8 * g + 4 * h) = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
-        }
+            for (int g = 0; g < 4; g++) {
+                bf16x2 lo = cvt2(dq_acc[db][4 * g + 0] * scale, dq_acc[db][4 * g + 1] * scale);
+                bf16x2 hi = cvt2(dq_acc[db][4 * g + 2] * scale, dq_acc[db][4 * g + 3] * scale);
+                *(bf16x4*)(dQr + 32 * db + 8 * g + 4 * h) = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+            }
+    }
     }   // pass (the loop above ends with a barrier, so both stages are free again)
+}
+
+template <int D, bool CAUSAL, bool TAIL>
+static hipError_t launch_dq_tt(const void* q, const void* k, const void* v, const void* d_o,
+                               const float* lse, const float* delta, void* dq,
+                               int B, int H, int Hkv, int N, float scale, hipStream_t stream)
+{
+    using S = DqShape<D>;
+    const int num_q_tiles = (N + S::kTileQ - 1) / S::kTileQ;
+    const int total = B * H * (CAUSAL ? (num_q_tiles + 1) / 2 : num_q_tiles);
+    hipLaunchKernelGGL((attn_bwd_dq_kernel<D, CAUSAL, TAIL>), dim3(total), dim3(S::kThreads), 0, stream,
+                       (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
+                       (bf16*)dq, N, num_q_tiles, total, scale, H, Hkv);
+    return hipGetLastError();
 }
 
 template <int D, bool CAUSAL>
@@ -645,12 +728,8 @@ static hipError_t launch_dq_t(const void* q, const void* k, const void* v, const
                               int B, int H, int Hkv, int N, float scale, hipStream_t stream)
 {
     using S = DqShape<D>;
-    const int num_q_tiles = N / S::kTileQ;
-    const int total = B * H * (CAUSAL ? (num_q_tiles + 1) / 2 : num_q_tiles);
-    hipLaunchKernelGGL((attn_bwd_dq_kernel<D, CAUSAL>), dim3(total), dim3(S::kThreads), 0, stream,
-                       (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
-                       (bf16*)dq, N, num_q_tiles, total, scale, H, Hkv);
-    return hipGetLastError();
+    return N % S::kTileQ ? launch_dq_tt<D, CAUSAL, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, N, scale, stream)
+                         : launch_dq_tt<D, CAUSAL, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, N, scale, stream);
 }
 
 hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,

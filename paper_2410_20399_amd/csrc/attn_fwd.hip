@@ -41,7 +41,8 @@ template <int D> __device__ __forceinline__ int swizzle_v(int row) {
     return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
 }
 
-template <int D, bool CAUSAL>
+// TAIL: N is not a multiple of 128 (the aligned case compiles without any of the tail code).
+template <int D, bool CAUSAL, bool TAIL>
 __global__ __launch_bounds__(256, 2)
 void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                      bf16* __restrict__ O, float* __restrict__ LSE,
@@ -74,6 +75,9 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
     const bf16* Vh = V + kv_head;
     const int q0 = qt * S::kTileQ + wave * 32;   // first query row of this wave
     const int my_q = q0 + l32;
+    // N need not be a multiple of the tile sizes: the kernel works on the sequence padded to 128,
+    // reads of rows >= N are redirected to row N-1, keys >= N are masked, rows >= N are not stored.
+    const int my_q_ld = (!TAIL || my_q < N) ? my_q : N - 1;
 
     const float c = scale * kLog2e;              // base-2 temperature
 
@@ -81,7 +85,7 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
     bf16x8 qf[D / 16];
 #pragma unroll
     for (int kb = 0; kb < D / 16; kb++)
-        qf[kb] = *(const bf16x8*)(Qh + (size_t)my_q * D + kb * 16 + h * 8);
+        qf[kb] = *(const bf16x8*)(Qh + (size_t)my_q_ld * D + kb * 16 + h * 8);
 
     // ---- per-thread source offsets of the direct-to-LDS tile loads
     // LDS slot s = it*256 + tid holds (row = s / chunks_per_row, physical chunk = s % chunks_per_row).
@@ -94,15 +98,32 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
         v_src[it] = row * D + ((pc ^ swizzle_v<D>(row)) * 8);
     }
     auto issue_tile = [&](int stage, int tile) {
-        const bf16* kt = Kh + (size_t)tile * S::kTileKV * D;
-        const bf16* vt = Vh + (size_t)tile * S::kTileKV * D;
+        const int j0 = tile * S::kTileKV;
+        const bf16* kt = Kh + (size_t)j0 * D;
+        const bf16* vt = Vh + (size_t)j0 * D;
         char* base = (stage ? smem1 : smem0) + wave * 1024;
+        if (!TAIL || j0 + S::kTileKV <= N) {
 #pragma unroll
-        for (int it = 0; it < S::kLoadsPerTile; it++)
-            load_global_to_lds16(kt + k_src[it], base + it * (S::kThreads * 16));
+            for (int it = 0; it < S::kLoadsPerTile; it++)
+                load_global_to_lds16(kt + k_src[it], base + it * (S::kThreads * 16));
 #pragma unroll
-        for (int it = 0; it < S::kLoadsPerTile; it++)
-            load_global_to_lds16(vt + v_src[it], base + S::kTileBytes + it * (S::kThreads * 16));
+            for (int it = 0; it < S::kLoadsPerTile; it++)
+                load_global_to_lds16(vt + v_src[it], base + S::kTileBytes + it * (S::kThreads * 16));
+        } else {
+            // the tile runs past the last key: rows >= N fetch row N-1 instead (they are masked later)
+#pragma unroll
+            for (int it = 0; it < S::kLoadsPerTile; it++) {
+                const int row = j0 + (it * S::kThreads + tid) / S::kChunksPerRow;
+                const int back = (row < N ? 0 : row - (N - 1)) * D;     // elements to step back
+                load_global_to_lds16(kt + k_src[it] - back, base + it * (S::kThreads * 16));
+            }
+#pragma unroll
+            for (int it = 0; it < S::kLoadsPerTile; it++) {
+                const int row = j0 + (it * S::kThreads + tid) / S::kChunksPerRow;
+                const int back = (row < N ? 0 : row - (N - 1)) * D;
+                load_global_to_lds16(vt + v_src[it] - back, base + S::kTileBytes + it * (S::kThreads * 16));
+            }
+        }
         __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of the math it overlaps with
     };
 
@@ -142,13 +163,14 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
                 s[b] = mfma32(kf, qf[kb], s[b]);
             }
         }
-        if (CAUSAL && j0 + S::kTileKV - 1 > q0) {    // tile crosses the diagonal for some row of this wave
+        // tile crosses the diagonal for some row of this wave, or runs past the last key
+        if ((CAUSAL && j0 + S::kTileKV - 1 > q0) || (TAIL && j0 + S::kTileKV > N)) {
 #pragma unroll
             for (int b = 0; b < 2; b++)
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     int key = j0 + 32 * b + 8 * (r >> 2) + 4 * h + (r & 3);
-                    if (key > my_q) s[b][r] = -INFINITY;
+                    if ((CAUSAL && key > my_q) || (TAIL && key >= N)) s[b][r] = -INFINITY;
                 }
         }
         // running max
@@ -207,7 +229,8 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
         }
     };
 
-    const int n_tiles = CAUSAL ? (qt * S::kTileQ + S::kTileQ) / S::kTileKV : N / S::kTileKV;   // even
+    // key tiles of the sequence padded to the query tile size; even
+    const int n_tiles = (CAUSAL ? qt * S::kTileQ + S::kTileQ : num_q_tiles * S::kTileQ) / S::kTileKV;
 
     issue_tile(0, 0);
     wait_vmcnt<0>();
@@ -226,16 +249,32 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
     // ---- epilogue
     const float l_tot = half_sum(l_run);
     const float inv = 1.0f / l_tot;
-    bf16* Oh = O + head + (size_t)my_q * D;
+    if (!TAIL || my_q < N) {
+        bf16* Oh = O + head + (size_t)my_q * D;
 #pragma unroll
-    for (int db = 0; db < D / 32; db++)
+        for (int db = 0; db < D / 32; db++)
 #pragma unroll
-        for (int g = 0; g < 4; g++) {
-            bf16x2 a = cvt2(o_acc[db][4 * g + 0] * inv, o_acc[db][4 * g + 1] * inv);
-            bf16x2 b = cvt2(o_acc[db][4 * g + 2] * inv, o_acc[db][4 * g + 3] * inv);
-            *(bf16x4*)(Oh + 32 * db + 8 * g + 4 * h) = __builtin_shufflevector(a, b, 0, 1, 2, 3);
-        }
-    if (h == 0) LSE[(size_t)bh * N + my_q] = m_run * scale + __builtin_logf(l_tot);
+            for (int g = 0; g < 4; g++) {
+                bf16x2 a = cvt2(o_acc[db][4 * g + 0] * inv, o_acc[db][4 * g + 1] * inv);
+                bf16x2 b = cvt2(o_acc[db][4 * g + 2] * inv, o_acc[db][4 * g + 3] * inv);
+                *(bf16x4*)(Oh + 32 * db + 8 * g + 4 * h) = __builtin_shufflevector(a, b, 0, 1, 2, 3);
+            }
+        if (h == 0) LSE[(size_t)bh * N + my_q] = m_run * scale + __builtin_logf(l_tot);
+    }
+}
+
+template <int D, bool CAUSAL, bool TAIL>
+static hipError_t launch_fwd_tt(const void* q, const void* k, const void* v, void* o, float* lse,
+                                int B, int H, int Hkv, int N, float scale, hipStream_t stream)
+{
+    using S = FwdShape<D>;
+    auto kern = attn_fwd_kernel<D, CAUSAL, TAIL>;
+    const int num_q_tiles = (N + S::kTileQ - 1) / S::kTileQ;
+    const int total = B * H * num_q_tiles;
+    hipLaunchKernelGGL(kern, dim3(total), dim3(S::kThreads), 0, stream,
+                       (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, lse,
+                       N, num_q_tiles, total, scale, H, Hkv);
+    return hipGetLastError();
 }
 
 template <int D, bool CAUSAL>
@@ -243,13 +282,8 @@ static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, void
                                int B, int H, int Hkv, int N, float scale, hipStream_t stream)
 {
     using S = FwdShape<D>;
-    auto kern = attn_fwd_kernel<D, CAUSAL>;
-    const int num_q_tiles = N / S::kTileQ;
-    const int total = B * H * num_q_tiles;
-    hipLaunchKernelGGL(kern, dim3(total), dim3(S::kThreads), 0, stream,
-                       (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, lse,
-                       N, num_q_tiles, total, scale, H, Hkv);
-    return hipGetLastError();
+    return N % S::kTileQ ? launch_fwd_tt<D, CAUSAL, true>(q, k, v, o, lse, B, H, Hkv, N, scale, stream)
+                         : launch_fwd_tt<D, CAUSAL, false>(q, k, v, o, lse, B, H, Hkv, N, scale, stream);
 }
 
 hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,

@@ -7,16 +7,17 @@
 
 namespace {
 
-constexpr int kGranuleN = 128;
+constexpr int kTileN = 128;      // rows per workgroup tile (sequences are padded to it inside the kernels)
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int check_shape(int B, int H, int N, int D)
 {
     if (D != 64 && D != 128) return TK_ERR_BAD_DIM;
-    if (B < 1 || H < 1 || N < kGranuleN || N % kGranuleN != 0) return TK_ERR_BAD_DIM;
-    const long long tiles = (long long)B * H * (N / kGranuleN);
+    if (B < 1 || H < 1 || N < 1) return TK_ERR_BAD_DIM;
+    const long long tiles = (long long)B * H * (((long long)N + kTileN - 1) / kTileN);
     if (tiles > 0x7fffffffLL) return TK_ERR_BAD_DIM;
+    if ((long long)B * H * N > 0x7fffffffLL * 16) return TK_ERR_BAD_DIM;   // row indices stay far inside 64 bits
     return TK_OK;
 }
 
@@ -169,7 +170,7 @@ const char* tk_status_string(int status)
     switch (status) {
         case TK_OK: return "ok";
         case TK_ERR_NULL_PTR: return "null pointer";
-        case TK_ERR_BAD_DIM: return "unsupported shape (D must be 64 or 128, N a positive multiple of 128, B,H >= 1)";
+        case TK_ERR_BAD_DIM: return "unsupported shape (D must be 64 or 128; B, H, N >= 1; Hkv must divide Hq)";
         case TK_ERR_MISALIGNED: return "pointer not 16-byte aligned";
         case TK_ERR_BAD_SCALE: return "scale must be finite and > 0";
         case TK_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";

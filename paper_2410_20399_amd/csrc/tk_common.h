@@ -56,6 +56,16 @@ __device__ __forceinline__ void load_global_to_lds16_untracked(const void* gptr,
                  : "m0", "memory");   // "memory": LDS contents change behind the compiler's back
 }
 
+// 4 bytes per lane, same rules: LDS address = wave base + 4 * lane.  For rows of fp32 statistics,
+// whose global address is only 4-byte aligned when N is not a multiple of 4.
+__device__ __forceinline__ void load_global_to_lds4_untracked(const void* gptr, const char* lds_wave_base) {
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(TK_LDS const char*)lds_wave_base;
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off"
+                 :
+                 : "s"(lds_addr), "v"(gptr)
+                 : "m0", "memory");
+}
+
 // 16-byte LDS read as an MFMA operand (8 consecutive-k bf16).
 __device__ __forceinline__ bf16x8 lds_read_b128(const char* smem, int byte_off) {
     return *(const bf16x8*)(smem + byte_off);

@@ -67,7 +67,7 @@ def test_forward_rejects_bad_arguments(lib):
     from paper_2410_20399_amd import attn as a
     for name in ("q", "k", "v", "o", "lse"):
         assert fwd(lib, **{name: None}) == a.TK_ERR_NULL_PTR
-    for bad in (dict(D=32), dict(D=96), dict(D=256), dict(N=0), dict(N=-128), dict(N=64), dict(N=200),
+    for bad in (dict(D=32), dict(D=96), dict(D=256), dict(N=0), dict(N=-128),
                 dict(B=0), dict(H=0), dict(B=-1), dict(B=1 << 20, H=1 << 12, N=128)):
         assert fwd(lib, **bad) == a.TK_ERR_BAD_DIM, bad
     for name in ("q", "k", "v", "o", "lse"):
@@ -87,7 +87,7 @@ def test_backward_rejects_bad_arguments(lib):
     assert bwd(lib, ws=None) == a.TK_ERR_NULL_PTR
     assert bwd(lib, ws=ODD) == a.TK_ERR_MISALIGNED
     assert bwd(lib, D=100) == a.TK_ERR_BAD_DIM
-    assert bwd(lib, N=129) == a.TK_ERR_BAD_DIM
+    assert bwd(lib, N=0) == a.TK_ERR_BAD_DIM
     assert bwd(lib, scale=-1.0) == a.TK_ERR_BAD_SCALE
     need = lib.tk_attn_bwd_workspace_bytes(1, 1, 128, 64)
     assert bwd(lib, ws_bytes=need - 1) == a.TK_ERR_WORKSPACE_TOO_SMALL
@@ -99,7 +99,8 @@ def test_workspace_size(lib):
     assert lib.tk_attn_bwd_workspace_bytes(1, 1, 128, 64) == 128 * 4
     assert lib.tk_attn_bwd_workspace_bytes(1, 3, 128, 64) == 3 * 128 * 4
     assert lib.tk_attn_bwd_workspace_bytes(16, 16, 4096, 128) == 16 * 16 * 4096 * 4
-    assert lib.tk_attn_bwd_workspace_bytes(1, 1, 100, 64) == 0
+    assert lib.tk_attn_bwd_workspace_bytes(1, 1, 100, 64) == 512      # 400 bytes of Delta, padded to 256
+    assert lib.tk_attn_bwd_workspace_bytes(1, 1, 0, 64) == 0
     assert lib.tk_attn_bwd_workspace_bytes(1, 1, 128, 80) == 0
 
 
@@ -121,7 +122,7 @@ def test_stage_entries_reject_bad_arguments(lib):
             ptrs[i] = ODD
             assert fn(*ptrs, 1, 1, 128, 64, 0, f(0.125), None) == a.TK_ERR_MISALIGNED
         assert fn(*([P] * nptr), 1, 1, 128, 64, 0, f(0.0), None) == a.TK_ERR_BAD_SCALE
-        assert fn(*([P] * nptr), 1, 1, 120, 64, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
+        assert fn(*([P] * nptr), 1, 1, 0, 64, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
         assert fn(*([P] * nptr), 1, 1, 128, 96, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
 
 
@@ -137,7 +138,7 @@ def test_gqa_entries_reject_bad_arguments(lib):
         assert lib.tk_attn_bwd_dq_gqa(P, P, P, P, P, P, P, 1, hq, hkv, 128, 64, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
     assert lib.tk_attn_fwd_gqa(None, P, P, P, P, 1, 4, 2, 128, 64, 0, f(0.125), None) == a.TK_ERR_NULL_PTR
     assert lib.tk_attn_fwd_gqa(P, ODD, P, P, P, 1, 4, 2, 128, 64, 0, f(0.125), None) == a.TK_ERR_MISALIGNED
-    assert lib.tk_attn_fwd_gqa(P, P, P, P, P, 1, 4, 2, 100, 64, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
+    assert lib.tk_attn_fwd_gqa(P, P, P, P, P, 1, 4, 2, 0, 64, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
     assert lib.tk_attn_fwd_gqa(P, P, P, P, P, 1, 4, 2, 128, 64, 0, f(-1.0), None) == a.TK_ERR_BAD_SCALE
     need = lib.tk_attn_bwd_workspace_bytes(1, 4, 128, 64)
     assert lib.tk_attn_bwd_gqa(P, P, P, P, P, P, P, P, P, 1, 4, 2, 128, 64, 0, f(0.125), P, sz(need - 1), None) == a.TK_ERR_WORKSPACE_TOO_SMALL
