@@ -369,6 +369,31 @@ int oracle_gqa_bwd(const double* q, const double* k, const double* v, const doub
     return fail ? -2 : 0;
 }
 
+/*
+ * Rotary positional encoding (the rotary kernel of the paper's appendix, head dimension D):
+ * with x1 = x[..., :D/2], x2 = x[..., D/2:] and one (sin, cos) pair per position and column,
+ *     o1 = x1 * cos - x2 * sin        o2 = x2 * cos + x1 * sin
+ * i.e. every pair (x1_c, x2_c) is rotated by the angle whose sine and cosine are given.
+ *   x, o : [BH][N][D]      sin, cos : [N][D/2]
+ */
+int oracle_rotary(const double* x, const double* sn, const double* cs, double* o, long BH, long N, long D)
+{
+    if (!x || !sn || !cs || !o || BH <= 0 || N <= 0 || D <= 0 || D % 2) return -1;
+    const long half = D / 2;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (long bh = 0; bh < BH; bh++)
+        for (long i = 0; i < N; i++) {
+            const double* xr = x + (bh * N + i) * D;
+            double* orow = o + (bh * N + i) * D;
+            for (long c = 0; c < half; c++) {
+                const double x1 = xr[c], x2 = xr[half + c];
+                orow[c] = x1 * cs[i * half + c] - x2 * sn[i * half + c];
+                orow[half + c] = x2 * cs[i * half + c] + x1 * sn[i * half + c];
+            }
+        }
+    return 0;
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

@@ -31,6 +31,8 @@ def _load():
         lib.oracle_attn_ds.argtypes = [dp, dp, dp, dp, dp, L, L, L, I, F]
         lib.oracle_gqa_fwd.argtypes = [dp, dp, dp, dp, dp, L, L, L, L, L, I, F]
         lib.oracle_gqa_bwd.argtypes = [dp, dp, dp, dp, dp, dp, dp, L, L, L, L, L, I, F]
+        lib.oracle_rotary.argtypes = [dp, dp, dp, dp, L, L, L]
+        lib.oracle_rotary.restype = ctypes.c_int
         for f in (lib.oracle_attn_fwd, lib.oracle_attn_fwd_rows, lib.oracle_attn_bwd,
                   lib.oracle_attn_ds, lib.oracle_gqa_fwd, lib.oracle_gqa_bwd, lib.oracle_num_threads):
             f.restype = ctypes.c_int
@@ -151,3 +153,19 @@ def gqa_bwd(q, k, v, d_o, causal: bool, scale: float):
     if rc:
         raise RuntimeError(f"oracle_gqa_bwd failed: {rc}")
     return dq, dk, dv
+
+
+def rotary(x, sin, cos):
+    """Rotary positional encoding: x [..., N, D], sin, cos [N, D/2] -> o [..., N, D] (float64).
+
+    o[..., :D/2] = x1 cos - x2 sin, o[..., D/2:] = x2 cos + x1 sin with x1, x2 the two halves of x."""
+    N, D = x.shape[-2:]
+    if sin.shape != (N, D // 2) or cos.shape != (N, D // 2) or D % 2:
+        raise ValueError("sin, cos must be [N, D/2]")
+    BH = int(np.prod(x.shape[:-2], dtype=np.int64)) if x.ndim > 2 else 1
+    x, xp = _c(x); sin, sp = _c(sin); cos, cp = _c(cos)
+    o = np.empty(x.shape, np.float64)
+    rc = _load().oracle_rotary(xp, sp, cp, _c(o)[1], BH, N, D)
+    if rc:
+        raise RuntimeError(f"oracle_rotary failed: {rc}")
+    return o
