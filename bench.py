@@ -25,12 +25,65 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (published: 2.5 PFLOP/s)
 HBM_PEAK_GBS = 8000.0
 
 
+def bench_rotary(args, attn, torch, dev, w, x):
+    """Rotary positional encoding on the workload's Q tensor: an HBM-bound stream (read x, write o)."""
+    B, H, N, D = w.B, w.H, w.N, w.D
+    g = torch.Generator().manual_seed(w.seed)
+    theta = torch.rand(N, D // 2, generator=g) * 8 - 4
+    sn, cs = torch.sin(theta).to(torch.bfloat16), torch.cos(theta).to(torch.bfloat16)
+    xd, snd, csd = x.to(dev), sn.to(dev), cs.to(dev)
+    o = torch.empty_like(xd)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        rc = attn.tk_rotary(xd, snd, csd, o, B, H, N, D, stream)
+        if rc != attn.TK_OK:
+            raise attn.TkAttnError(rc, "tk_rotary")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kernel_ms = e0.elapsed_time(e1) / args.steps
+    nbytes = 2 * B * H * N * D * 2 + 2 * N * (D // 2) * 2        # read x, write o, read both tables once
+    gbps = nbytes / (kernel_ms * 1e-3) / 1e9
+    out = {"metric": f"rotary GB/s (bf16, {w.name})", "value": round(nbytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "rotary_" + w.name, "B": B, "H": H, "N": N, "D": D},
+           "roofline": {"kernel": "rotary_kernel", "bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBS, 4), "traffic": None, "bytes_per_launch": nbytes}}
+    if not args.no_cpu_baseline:
+        from oracle import attn_oracle as orc
+        nh = min(B * H, 64)
+        xs = x.reshape(B * H, N, D)[:nh].double().numpy()
+        c0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - c0 < min(args.cpu_seconds, 5.0):
+            orc.rotary(xs, sn.double().numpy(), cs.double().numpy())
+            reps += 1
+        spent = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": round(reps * nh * N * D * 2 * 2 / spent / 1e9, 2), "unit": "GB/s (of bf16-sized traffic)",
+                               "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"fp64 oracle on {nh} of {B * H} heads, {reps} passes, {spent:.1f} s"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=6, help="index into workloads.WORKLOADS (default: the target shape)")
+    ap.add_argument("--op", choices=["attention", "rotary"], default="attention",
+                    help="attention (default: the headline fwd+bwd step) or the rotary kernel on the same tensor shape")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle sample")
     ap.add_argument("--no-mfma-probe", action="store_true", help="skip the bare-MFMA ceiling measurement")
@@ -55,6 +108,8 @@ def main():
     q, k, v, d_o = workloads.make_inputs(w, need_do=True)
     qd, kd, vd, dod = (t.to(dev) for t in (q, k, v, d_o))
     B, H, N, D = w.B, w.H, w.N, w.D
+    if args.op == "rotary":
+        return bench_rotary(args, attn, torch, dev, w, q)
     Hkv = w.kv_heads                          # == H unless the workload is grouped-query
     o = torch.empty_like(qd)
     lse = torch.empty((B, H, N), dtype=torch.float32, device=dev)

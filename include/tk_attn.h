@@ -159,6 +159,21 @@ int tk_attn_bwd_dq_gqa(const void* q, const void* k, const void* v, const void* 
                        int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream);
 
 /*
+ * Rotary positional encoding (the rotary kernel of the paper's appendix; applied to Q and K ahead
+ * of attention).  With x1 = x[..., :D/2] and x2 = x[..., D/2:]:
+ *
+ *   o[..., :D/2] = x1 * cos - x2 * sin          o[..., D/2:] = x2 * cos + x1 * sin
+ *
+ *   x              : in,  bf16 [B,H,N,D]
+ *   sin_table,
+ *   cos_table      : in,  bf16 [N, D/2] (one angle per position and column pair, shared by all heads)
+ *   o              : out, bf16 [B,H,N,D]; may be the same buffer as x (in place), no other overlap
+ * fp32 arithmetic, one rounding to bf16.  D is 64 or 128, any N >= 1.
+ */
+int tk_rotary(const void* x, const void* sin_table, const void* cos_table, void* o,
+              int B, int H, int N, int D, void* stream);
+
+/*
  * Measurement aid, not part of the attention path: a bare stream of the bf16 MFMA that the
  * attention kernels use, on caller-supplied operand values.  The benchmark times it to report the
  * matrix-pipe rate the chip sustains with the same kind of data (the clock it holds depends on

@@ -23,7 +23,7 @@ TK_ERR_LAUNCH = -6
 
 EXPORTS = ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
            "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_attn_fwd_gqa", "tk_attn_bwd_gqa", "tk_attn_bwd_dkdv_gqa",
-           "tk_attn_bwd_dq_gqa", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
+           "tk_attn_bwd_dq_gqa", "tk_rotary", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
 
 _lib = None
 
@@ -65,6 +65,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.tk_attn_bwd_dkdv_gqa.restype = i
     lib.tk_attn_bwd_dq_gqa.argtypes = [vp, vp, vp, vp, fp, fp, vp, i, i, i, i, i, i, f, vp]
     lib.tk_attn_bwd_dq_gqa.restype = i
+    lib.tk_rotary.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
+    lib.tk_rotary.restype = i
     lib.tk_mfma_probe.argtypes = [vp, fp, i, i, vp]
     lib.tk_mfma_probe.restype = i
     lib.tk_status_string.argtypes = [i]
@@ -159,6 +161,10 @@ def tk_attn_bwd_dq_gqa(q, k, v, d_o, lse, delta, dq, B, Hq, Hkv, N, D, causal, s
     return load_library().tk_attn_bwd_dq_gqa(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(delta),
                                              _ptr(dq), B, Hq, Hkv, N, D, int(bool(causal)), float(scale),
                                              _stream(stream))
+
+
+def tk_rotary(x, sin_table, cos_table, o, B, H, N, D, stream=None) -> int:
+    return load_library().tk_rotary(_ptr(x), _ptr(sin_table), _ptr(cos_table), _ptr(o), B, H, N, D, _stream(stream))
 
 
 def tk_mfma_probe(operands, sink, workgroups, iters, stream=None) -> int:
@@ -256,3 +262,17 @@ def gqa_bwd(q, k, v, o, d_o, lse, causal: bool, scale: float, workspace=None, st
     if rc != TK_OK:
         raise TkAttnError(rc, "tk_attn_bwd_gqa")
     return dq, dk, dv
+
+
+def rotary(x, sin_table, cos_table, out=None, stream=None):
+    """Rotary positional encoding: x bf16 [B,H,N,D], sin/cos bf16 [N, D/2]. Returns o (out=x works in place)."""
+    _check_bf16("x", x)
+    B, H, N, D = x.shape
+    _check_bf16("sin_table", sin_table, (N, D // 2))
+    _check_bf16("cos_table", cos_table, (N, D // 2))
+    o = torch.empty_like(x) if out is None else out
+    _check_bf16("o", o, x.shape)
+    rc = tk_rotary(x, sin_table, cos_table, o, B, H, N, D, stream)
+    if rc != TK_OK:
+        raise TkAttnError(rc, "tk_rotary")
+    return o

@@ -156,6 +156,16 @@ int tk_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
                            workspace, workspace_bytes, stream);
 }
 
+int tk_rotary(const void* x, const void* sin_table, const void* cos_table, void* o,
+              int B, int H, int N, int D, void* stream)
+{
+    if (!x || !sin_table || !cos_table || !o) return TK_ERR_NULL_PTR;
+    if (int rc = check_shape(B, H, N, D)) return rc;
+    if (!aligned16(x) || !aligned16(sin_table) || !aligned16(cos_table) || !aligned16(o)) return TK_ERR_MISALIGNED;
+    hipError_t e = tk::launch_rotary(x, sin_table, cos_table, o, B, H, N, D, (hipStream_t)stream);
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
 int tk_mfma_probe(const void* operands, float* sink, int workgroups, int iters, void* stream)
 {
     if (!operands || !sink) return TK_ERR_NULL_PTR;

@@ -32,6 +32,10 @@ hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const
                               const float* lse, const float* delta, void* dq,
                               int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream);
 
+// rotary positional encoding: x, o [B,H,N,D]; sin, cos [N, D/2]
+hipError_t launch_rotary(const void* x, const void* sn, const void* cs, void* o,
+                         int B, int H, int N, int D, hipStream_t stream);
+
 // bare MFMA stream (measurement aid): 32 MFMAs per wave per iteration
 hipError_t launch_mfma_probe(const void* operands, float* sink, int workgroups, int iters, hipStream_t stream);
 

@@ -145,6 +145,18 @@ def test_gqa_entries_reject_bad_arguments(lib):
     assert lib.tk_attn_bwd_gqa(P, P, P, P, P, P, P, P, None, 1, 4, 2, 128, 64, 0, f(0.125), P, sz(need), None) == a.TK_ERR_NULL_PTR
 
 
+def test_rotary_rejects_bad_arguments(lib):
+    from paper_2410_20399_amd import attn as a
+    for i in range(4):
+        ptrs = [P] * 4
+        ptrs[i] = None
+        assert lib.tk_rotary(*ptrs, 1, 1, 128, 64, None) == a.TK_ERR_NULL_PTR
+        ptrs[i] = ODD
+        assert lib.tk_rotary(*ptrs, 1, 1, 128, 64, None) == a.TK_ERR_MISALIGNED
+    assert lib.tk_rotary(P, P, P, P, 1, 1, 128, 96, None) == a.TK_ERR_BAD_DIM
+    assert lib.tk_rotary(P, P, P, P, 1, 1, 0, 128, None) == a.TK_ERR_BAD_DIM
+
+
 def test_mfma_probe_rejects_bad_arguments(lib):
     from paper_2410_20399_amd import attn as a
     assert lib.tk_mfma_probe(None, P, 1, 1, None) == a.TK_ERR_NULL_PTR
