@@ -394,6 +394,38 @@ int oracle_rotary(const double* x, const double* sn, const double* cs, double* o
     return 0;
 }
 
+/*
+ * Matrix multiply (the GEMM kernel of the paper's appendix): C = A B with A [M][K], B [K][N],
+ * C [M][N], all row-major.  The plain definition, one dot product per output element.
+ */
+int oracle_gemm(const double* a, const double* b, double* c, long M, long N, long K)
+{
+    if (!a || !b || !c || M <= 0 || N <= 0 || K <= 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (long i = 0; i < M; i++)
+        for (long j = 0; j < N; j++) {
+            double acc = 0.0;
+            for (long k = 0; k < K; k++) acc += a[i * K + k] * b[k * N + j];
+            c[i * N + j] = acc;
+        }
+    return 0;
+}
+
+/* Selected elements of C = A B: out[e] = sum_k A[rows[e]][k] B[k][cols[e]] (for sampled checks of large products). */
+int oracle_gemm_elements(const double* a, const double* b, const long* rows, const long* cols, long n,
+                         double* out, long M, long N, long K)
+{
+    if (!a || !b || !rows || !cols || !out || n < 0 || M <= 0 || N <= 0 || K <= 0) return -1;
+    for (long e = 0; e < n; e++) if (rows[e] < 0 || rows[e] >= M || cols[e] < 0 || cols[e] >= N) return -1;
+#pragma omp parallel for schedule(static)
+    for (long e = 0; e < n; e++) {
+        double acc = 0.0;
+        for (long k = 0; k < K; k++) acc += a[rows[e] * K + k] * b[k * N + cols[e]];
+        out[e] = acc;
+    }
+    return 0;
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

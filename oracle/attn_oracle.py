@@ -31,6 +31,10 @@ def _load():
         lib.oracle_attn_ds.argtypes = [dp, dp, dp, dp, dp, L, L, L, I, F]
         lib.oracle_gqa_fwd.argtypes = [dp, dp, dp, dp, dp, L, L, L, L, L, I, F]
         lib.oracle_gqa_bwd.argtypes = [dp, dp, dp, dp, dp, dp, dp, L, L, L, L, L, I, F]
+        lib.oracle_gemm.argtypes = [dp, dp, dp, L, L, L]
+        lib.oracle_gemm.restype = ctypes.c_int
+        lib.oracle_gemm_elements.argtypes = [dp, dp, lp, lp, L, dp, L, L, L]
+        lib.oracle_gemm_elements.restype = ctypes.c_int
         lib.oracle_rotary.argtypes = [dp, dp, dp, dp, L, L, L]
         lib.oracle_rotary.restype = ctypes.c_int
         for f in (lib.oracle_attn_fwd, lib.oracle_attn_fwd_rows, lib.oracle_attn_bwd,
@@ -169,3 +173,34 @@ def rotary(x, sin, cos):
     if rc:
         raise RuntimeError(f"oracle_rotary failed: {rc}")
     return o
+
+
+def gemm(a, b):
+    """C = A B for A [M, K], B [K, N] (float64)."""
+    if a.ndim != 2 or b.ndim != 2 or a.shape[1] != b.shape[0]:
+        raise ValueError("a must be [M, K], b [K, N]")
+    M, K = a.shape
+    N = b.shape[1]
+    a, ap = _c(a); b, bp = _c(b)
+    c = np.empty((M, N), np.float64)
+    rc = _load().oracle_gemm(ap, bp, _c(c)[1], M, N, K)
+    if rc:
+        raise RuntimeError(f"oracle_gemm failed: {rc}")
+    return c
+
+
+def gemm_elements(a, b, rows, cols):
+    """Selected elements C[rows[e], cols[e]] of A B (float64)."""
+    if a.ndim != 2 or b.ndim != 2 or a.shape[1] != b.shape[0]:
+        raise ValueError("a must be [M, K], b [K, N]")
+    M, K = a.shape
+    N = b.shape[1]
+    a, ap = _c(a); b, bp = _c(b)
+    rows = np.ascontiguousarray(rows, dtype=np.int64); cols = np.ascontiguousarray(cols, dtype=np.int64)
+    out = np.empty((len(rows),), np.float64)
+    lp = ctypes.POINTER(ctypes.c_long)
+    rc = _load().oracle_gemm_elements(ap, bp, rows.ctypes.data_as(lp), cols.ctypes.data_as(lp), len(rows),
+                                      _c(out)[1], M, N, K)
+    if rc:
+        raise RuntimeError(f"oracle_gemm_elements failed: {rc}")
+    return out
