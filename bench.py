@@ -25,6 +25,57 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (published: 2.5 PFLOP/s)
 HBM_PEAK_GBS = 8000.0
 
 
+def bench_gemm(args, attn, torch, dev, M=8192, N=8192, K=8192):
+    """bf16 GEMM C = A B on normal data: a kernel of MFMAs and LDS traffic only (MFMA roofline)."""
+    g = torch.Generator().manual_seed(20399 + 840)
+    a = torch.randn(M, K, generator=g).to(torch.bfloat16)
+    b = torch.randn(K, N, generator=g).to(torch.bfloat16)
+    ad, bd = a.to(dev), b.to(dev)
+    c = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        rc = attn.tk_gemm(ad, bd, c, M, N, K, stream)
+        if rc != attn.TK_OK:
+            raise attn.TkAttnError(rc, "tk_gemm")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kernel_ms = e0.elapsed_time(e1) / args.steps
+    flops = 2.0 * M * N * K
+    tflops = flops / (kernel_ms * 1e-3) / 1e12
+    out = {"metric": f"bf16 GEMM TFLOPS (M=N=K={M})", "value": round(flops / (ms_per_step * 1e-3) / 1e12, 2), "unit": "TFLOP/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"gemm_{M}x{N}x{K}", "M": M, "N": N, "K": K},
+           "roofline": {"kernel": "gemm_kernel", "bound": "mfma", "achieved": round(tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                        "unit": "TFLOP/s", "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                        "flops_per_launch": flops}}
+    if not args.no_cpu_baseline:
+        from oracle import attn_oracle as orc
+        rows = min(M, 16)
+        a64, b64 = a[:rows].double().numpy(), b.double().numpy()
+        c0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - c0 < min(args.cpu_seconds, 10.0):
+            orc.gemm(a64, b64)
+            reps += 1
+        spent = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": round(reps * 2.0 * rows * N * K / spent / 1e12, 6), "unit": "TFLOP/s",
+                               "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"fp64 oracle on the first {rows} of {M} rows of C, {reps} passes, {spent:.1f} s"}
+    print(json.dumps(out))
+
+
 def bench_rotary(args, attn, torch, dev, w, x):
     """Rotary positional encoding on the workload's Q tensor: an HBM-bound stream (read x, write o)."""
     B, H, N, D = w.B, w.H, w.N, w.D
@@ -82,8 +133,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=6, help="index into workloads.WORKLOADS (default: the target shape)")
-    ap.add_argument("--op", choices=["attention", "rotary"], default="attention",
-                    help="attention (default: the headline fwd+bwd step) or the rotary kernel on the same tensor shape")
+    ap.add_argument("--op", choices=["attention", "rotary", "gemm"], default="attention",
+                    help="attention (default: the headline fwd+bwd step), the rotary kernel on the same tensor shape, "
+                         "or the bf16 GEMM (8192^3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle sample")
     ap.add_argument("--no-mfma-probe", action="store_true", help="skip the bare-MFMA ceiling measurement")
@@ -104,6 +156,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     dev = torch.device("cuda:0")
+    if args.op == "gemm":
+        return bench_gemm(args, attn, torch, dev)
     w = workloads.WORKLOADS[args.workload]
     q, k, v, d_o = workloads.make_inputs(w, need_do=True)
     qd, kd, vd, dod = (t.to(dev) for t in (q, k, v, d_o))

@@ -159,6 +159,16 @@ int tk_attn_bwd_dq_gqa(const void* q, const void* k, const void* v, const void* 
                        int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream);
 
 /*
+ * bf16 matrix multiply (the GEMM of the paper's appendix, second workload): C = A B with fp32
+ * accumulation and one rounding to bf16.
+ *
+ *   a : in,  bf16 [M, K] row-major        b : in, bf16 [K, N] row-major        c : out, bf16 [M, N] row-major
+ * M and N must be positive multiples of 256, K a positive multiple of 64 (TK_ERR_BAD_DIM otherwise).
+ * No workspace; the result is bit-reproducible (every element is one fixed-order accumulation).
+ */
+int tk_gemm(const void* a, const void* b, void* c, int M, int N, int K, void* stream);
+
+/*
  * Rotary positional encoding (the rotary kernel of the paper's appendix; applied to Q and K ahead
  * of attention).  With x1 = x[..., :D/2] and x2 = x[..., D/2:]:
  *

@@ -23,7 +23,7 @@ TK_ERR_LAUNCH = -6
 
 EXPORTS = ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
            "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_attn_fwd_gqa", "tk_attn_bwd_gqa", "tk_attn_bwd_dkdv_gqa",
-           "tk_attn_bwd_dq_gqa", "tk_rotary", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
+           "tk_attn_bwd_dq_gqa", "tk_rotary", "tk_gemm", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
 
 _lib = None
 
@@ -65,6 +65,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.tk_attn_bwd_dkdv_gqa.restype = i
     lib.tk_attn_bwd_dq_gqa.argtypes = [vp, vp, vp, vp, fp, fp, vp, i, i, i, i, i, i, f, vp]
     lib.tk_attn_bwd_dq_gqa.restype = i
+    lib.tk_gemm.argtypes = [vp, vp, vp, i, i, i, vp]
+    lib.tk_gemm.restype = i
     lib.tk_rotary.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     lib.tk_rotary.restype = i
     lib.tk_mfma_probe.argtypes = [vp, fp, i, i, vp]
@@ -161,6 +163,10 @@ def tk_attn_bwd_dq_gqa(q, k, v, d_o, lse, delta, dq, B, Hq, Hkv, N, D, causal, s
     return load_library().tk_attn_bwd_dq_gqa(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(delta),
                                              _ptr(dq), B, Hq, Hkv, N, D, int(bool(causal)), float(scale),
                                              _stream(stream))
+
+
+def tk_gemm(a, b, c, M, N, K, stream=None) -> int:
+    return load_library().tk_gemm(_ptr(a), _ptr(b), _ptr(c), M, N, K, _stream(stream))
 
 
 def tk_rotary(x, sin_table, cos_table, o, B, H, N, D, stream=None) -> int:
@@ -276,3 +282,18 @@ def rotary(x, sin_table, cos_table, out=None, stream=None):
     if rc != TK_OK:
         raise TkAttnError(rc, "tk_rotary")
     return o
+
+
+def gemm(a, b, out=None, stream=None):
+    """C = A B: a bf16 [M,K], b bf16 [K,N] -> c bf16 [M,N] (M, N multiples of 256, K of 64)."""
+    if a.dtype != torch.bfloat16 or b.dtype != torch.bfloat16 or a.dim() != 2 or b.dim() != 2:
+        raise ValueError("a, b must be 2-D bf16 tensors")
+    if not (a.is_cuda and b.is_cuda and a.is_contiguous() and b.is_contiguous()) or a.shape[1] != b.shape[0]:
+        raise ValueError("a [M,K], b [K,N] must be contiguous CUDA tensors")
+    M, K = a.shape
+    N = b.shape[1]
+    c = torch.empty((M, N), dtype=torch.bfloat16, device=a.device) if out is None else out
+    rc = tk_gemm(a, b, c, M, N, K, stream)
+    if rc != TK_OK:
+        raise TkAttnError(rc, "tk_gemm")
+    return c

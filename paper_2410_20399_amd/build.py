@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtk_attn.so")
-SOURCES = ["tk_attn_api.hip", "attn_fwd.hip", "attn_bwd.hip", "mfma_probe.hip", "rotary.hip"]
+SOURCES = ["tk_attn_api.hip", "attn_fwd.hip", "attn_bwd.hip", "mfma_probe.hip", "rotary.hip", "gemm.hip"]
 HEADERS = ["tk_common.h", "tk_launch.h", os.path.join("..", "..", "include", "tk_attn.h")]
 
 FLAGS = [

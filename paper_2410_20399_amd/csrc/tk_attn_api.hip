@@ -156,6 +156,16 @@ int tk_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
                            workspace, workspace_bytes, stream);
 }
 
+int tk_gemm(const void* a, const void* b, void* c, int M, int N, int K, void* stream)
+{
+    if (!a || !b || !c) return TK_ERR_NULL_PTR;
+    if (M < 256 || N < 256 || K < 64 || M % 256 || N % 256 || K % 64) return TK_ERR_BAD_DIM;
+    if ((long long)(M / 256) * (N / 256) > 0x7fffffffLL) return TK_ERR_BAD_DIM;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return TK_ERR_MISALIGNED;
+    hipError_t e = tk::launch_gemm(a, b, c, M, N, K, (hipStream_t)stream);
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
 int tk_rotary(const void* x, const void* sin_table, const void* cos_table, void* o,
               int B, int H, int N, int D, void* stream)
 {

@@ -32,6 +32,9 @@ hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const
                               const float* lse, const float* delta, void* dq,
                               int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream);
 
+// bf16 matrix multiply C = A B: A [M,K], B [K,N], C [M,N] row-major; M, N multiples of 256, K of 64
+hipError_t launch_gemm(const void* a, const void* b, void* c, int M, int N, int K, hipStream_t stream);
+
 // rotary positional encoding: x, o [B,H,N,D]; sin, cos [N, D/2]
 hipError_t launch_rotary(const void* x, const void* sn, const void* cs, void* o,
                          int B, int H, int N, int D, hipStream_t stream);

@@ -145,6 +145,18 @@ def test_gqa_entries_reject_bad_arguments(lib):
     assert lib.tk_attn_bwd_gqa(P, P, P, P, P, P, P, P, None, 1, 4, 2, 128, 64, 0, f(0.125), P, sz(need), None) == a.TK_ERR_NULL_PTR
 
 
+def test_gemm_rejects_bad_arguments(lib):
+    from paper_2410_20399_amd import attn as a
+    for i in range(3):
+        ptrs = [P] * 3
+        ptrs[i] = None
+        assert lib.tk_gemm(*ptrs, 256, 256, 64, None) == a.TK_ERR_NULL_PTR
+        ptrs[i] = ODD
+        assert lib.tk_gemm(*ptrs, 256, 256, 64, None) == a.TK_ERR_MISALIGNED
+    for M, N, K in ((0, 256, 64), (128, 256, 64), (256, 300, 64), (256, 256, 32), (256, 256, 100), (-256, 256, 64)):
+        assert lib.tk_gemm(P, P, P, M, N, K, None) == a.TK_ERR_BAD_DIM, (M, N, K)
+
+
 def test_rotary_rejects_bad_arguments(lib):
     from paper_2410_20399_amd import attn as a
     for i in range(4):
