@@ -139,6 +139,17 @@ void gemm_kernel(const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* _
             for (int a = 0; a < 4; a++) acc[b][a] = mfma32(bfr[set][b], af[set][a], acc[b][a]);
     };
 
+    // schedule of one sub-step: the 12 fragment reads go out one per MFMA, ahead of the remaining MFMAs
+    auto interleave = [&]() {
+#pragma unroll
+        for (int i = 0; i < 12; i++) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
     const int n_steps = K / S::kTileK;
     issue_stage(0);
     if (n_steps > 1) issue_stage(1);
@@ -152,13 +163,13 @@ void gemm_kernel(const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* _
         // sub-steps 0..2: multiply one set while the next sub-step's fragments are read into the other
         read_frags(1, s, 1);
         multiply(0);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave();
         read_frags(0, s, 2);
         multiply(1);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave();
         read_frags(1, s, 3);
         multiply(0);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave();
         // every wave holds its last fragments of this stage in registers: the stage can be refilled.
         // The next stage (issued one step ago) must have landed before its first fragments are read.
         wait_vmcnt<0>();
@@ -168,7 +179,7 @@ void gemm_kernel(const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* _
         __builtin_amdgcn_sched_barrier(0);
         if (s + 1 < n_steps) read_frags(0, s + 1, 0);
         multiply(1);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave();
     }
 
     // ---- epilogue: lane <-> row of C; register r of block (b, a) <-> column 32b + 8*(r/4) + 4h + r%4
