@@ -37,6 +37,9 @@
  * The grouped-query functions at the end of the file are pinned to the
  * per-head ones (keys/values repeated per group, gradients summed over the
  * group), to a brute-force numpy softmax and to finite differences.
+ * The functions for different query and key lengths (tests/test_oracle_rect_pins.py) are
+ * pinned to a library softmax, to the last rows of the square causal problem they are cut
+ * from, to closed forms for equal keys and one query, and to finite differences.
  *
  * Build: gcc -O2 -fopenmp -shared -fPIC attn_oracle.c -o liboracle_attn.so -lm
  */
@@ -358,6 +361,159 @@ int oracle_gqa_bwd(const double* q, const double* k, const double* v, const doub
                         double ds = p * (dp - delta[bh * N + i]);
                         for (long d = 0; d < D; d++) {
                             dv_j[d] += p * doh[i * D + d];
+                            dk_j[d] += ds * qh[i * D + d];
+                        }
+                    }
+                }
+                for (long d = 0; d < D; d++) dk_j[d] *= scale;
+            }
+    }
+    free(delta); free(lse);
+    return fail ? -2 : 0;
+}
+
+/*
+ * Attention with different numbers of queries and keys (cross attention, decoding against a
+ * longer key/value history).  The paper's listings take one sequence length; its Appendix B.3
+ * kernel guards only the query tail.  Reading taken: q has Nq rows, k and v have Nk rows, every
+ * sum over keys runs over the Nk keys.  With the causal mask the two sequences are aligned at
+ * their ENDS: query i is position i + (Nk - Nq) of the key sequence and attends to keys
+ * j <= i + (Nk - Nq), so the last query sees every key and Nq = Nk gives the usual mask.  The
+ * causal case needs Nq <= Nk (otherwise the first queries would see no key at all).
+ * Heads may be grouped as above.
+ *   q, d_o, o, dq : [B][Hq][Nq][D]     k, v, dk, dv : [B][Hkv][Nk][D]     lse : [B][Hq][Nq]
+ */
+static long visible_rect(long i, long Nq, long Nk, int causal) { return causal ? i + (Nk - Nq) + 1 : Nk; }
+
+/* scores of query row q_i against keys 0..nj-1 -> p[j] = softmax probabilities, *lse_i = ln sum exp */
+static void softmax_row_rect(const double* q_i, const double* k, long nj, long D, double scale, double* p, double* lse_i)
+{
+    double m = -INFINITY, l = 0.0;
+    for (long j = 0; j < nj; j++) {
+        double dot = 0.0;
+        for (long d = 0; d < D; d++) dot += q_i[d] * k[j * D + d];
+        p[j] = scale * dot;
+        if (p[j] > m) m = p[j];
+    }
+    for (long j = 0; j < nj; j++) { p[j] = exp(p[j] - m); l += p[j]; }
+    for (long j = 0; j < nj; j++) p[j] /= l;
+    *lse_i = m + log(l);
+}
+
+static int rect_args_bad(long B, long Hq, long Hkv, long Nq, long Nk, long D, int causal)
+{
+    return B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv || Nq <= 0 || Nk <= 0 || D <= 0 || (causal && Nq > Nk);
+}
+
+int oracle_rect_fwd(const double* q, const double* k, const double* v, double* o, double* lse,
+                    long B, long Hq, long Hkv, long Nq, long Nk, long D, int causal, double scale)
+{
+    if (!q || !k || !v || !o || !lse || rect_args_bad(B, Hq, Hkv, Nq, Nk, D, causal)) return -1;
+    const long G = Hq / Hkv;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double* p = (double*)malloc((size_t)Nk * sizeof(double));
+        if (!p) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for collapse(2) schedule(dynamic, 16)
+            for (long bh = 0; bh < B * Hq; bh++)
+                for (long i = 0; i < Nq; i++) {
+                    const long kvh = (bh / Hq) * Hkv + (bh % Hq) / G;
+                    const double* kh = k + kvh * Nk * D;
+                    const double* vh = v + kvh * Nk * D;
+                    const long nj = visible_rect(i, Nq, Nk, causal);
+                    softmax_row_rect(q + (bh * Nq + i) * D, kh, nj, D, scale, p, lse + bh * Nq + i);
+                    double* o_i = o + (bh * Nq + i) * D;
+                    for (long d = 0; d < D; d++) o_i[d] = 0.0;
+                    for (long j = 0; j < nj; j++)
+                        for (long d = 0; d < D; d++) o_i[d] += p[j] * vh[j * D + d];
+                }
+            free(p);
+        }
+    }
+    return fail ? -2 : 0;
+}
+
+int oracle_rect_bwd(const double* q, const double* k, const double* v, const double* d_o,
+                    double* dq, double* dk, double* dv,
+                    long B, long Hq, long Hkv, long Nq, long Nk, long D, int causal, double scale)
+{
+    if (!q || !k || !v || !d_o || !dq || !dk || !dv || rect_args_bad(B, Hq, Hkv, Nq, Nk, D, causal)) return -1;
+    const long G = Hq / Hkv;
+    double* delta = (double*)malloc((size_t)B * Hq * Nq * sizeof(double));
+    double* lse = (double*)malloc((size_t)B * Hq * Nq * sizeof(double));
+    if (!delta || !lse) { free(delta); free(lse); return -2; }
+    int fail = 0;
+
+    /* sweep 1: per query row -> LSE_i, O_i, Delta_i = dO_i . O_i, dQ_i = scale * sum_j dS_ij K_j */
+#pragma omp parallel
+    {
+        double* p = (double*)malloc((size_t)Nk * sizeof(double));
+        double* o_i = (double*)malloc((size_t)D * sizeof(double));
+        if (!p || !o_i) {
+#pragma omp atomic write
+            fail = 1;
+        } else {
+#pragma omp for collapse(2) schedule(dynamic, 16)
+            for (long bh = 0; bh < B * Hq; bh++)
+                for (long i = 0; i < Nq; i++) {
+                    const long kvh = (bh / Hq) * Hkv + (bh % Hq) / G;
+                    const double* kh = k + kvh * Nk * D;
+                    const double* vh = v + kvh * Nk * D;
+                    const double* do_i = d_o + (bh * Nq + i) * D;
+                    const long nj = visible_rect(i, Nq, Nk, causal);
+                    softmax_row_rect(q + (bh * Nq + i) * D, kh, nj, D, scale, p, lse + bh * Nq + i);
+                    for (long d = 0; d < D; d++) o_i[d] = 0.0;
+                    for (long j = 0; j < nj; j++)
+                        for (long d = 0; d < D; d++) o_i[d] += p[j] * vh[j * D + d];
+                    double dl = 0.0;
+                    for (long d = 0; d < D; d++) dl += do_i[d] * o_i[d];
+                    delta[bh * Nq + i] = dl;
+                    double* dq_i = dq + (bh * Nq + i) * D;
+                    for (long d = 0; d < D; d++) dq_i[d] = 0.0;
+                    for (long j = 0; j < nj; j++) {
+                        double dp = 0.0;
+                        for (long d = 0; d < D; d++) dp += do_i[d] * vh[j * D + d];
+                        const double ds = p[j] * (dp - dl);
+                        for (long d = 0; d < D; d++) dq_i[d] += ds * kh[j * D + d];
+                    }
+                    for (long d = 0; d < D; d++) dq_i[d] *= scale;
+                }
+        }
+        free(p); free(o_i);
+    }
+
+    /* sweep 2: per key row -> dV_j = sum_i P_ij dO_i, dK_j = scale * sum_i dS_ij Q_i over the
+       queries that see key j (i + Nk - Nq >= j when causal) of every query head of the group */
+    if (!fail) {
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+        for (long bk = 0; bk < B * Hkv; bk++)
+            for (long j = 0; j < Nk; j++) {
+                const long b = bk / Hkv, hk = bk % Hkv;
+                const double* k_j = k + (bk * Nk + j) * D;
+                const double* v_j = v + (bk * Nk + j) * D;
+                double* dk_j = dk + (bk * Nk + j) * D;
+                double* dv_j = dv + (bk * Nk + j) * D;
+                for (long d = 0; d < D; d++) { dk_j[d] = 0.0; dv_j[d] = 0.0; }
+                long i0 = causal ? j - (Nk - Nq) : 0;
+                if (i0 < 0) i0 = 0;
+                for (long g = 0; g < G; g++) {
+                    const long bh = b * Hq + hk * G + g;
+                    const double* qh = q + bh * Nq * D;
+                    const double* doh = d_o + bh * Nq * D;
+                    for (long i = i0; i < Nq; i++) {
+                        double dot = 0.0, dp = 0.0;
+                        for (long d = 0; d < D; d++) {
+                            dot += qh[i * D + d] * k_j[d];
+                            dp += doh[i * D + d] * v_j[d];
+                        }
+                        const double pij = exp(scale * dot - lse[bh * Nq + i]);
+                        const double ds = pij * (dp - delta[bh * Nq + i]);
+                        for (long d = 0; d < D; d++) {
+                            dv_j[d] += pij * doh[i * D + d];
                             dk_j[d] += ds * qh[i * D + d];
                         }
                     }

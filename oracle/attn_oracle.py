@@ -31,6 +31,10 @@ def _load():
         lib.oracle_attn_ds.argtypes = [dp, dp, dp, dp, dp, L, L, L, I, F]
         lib.oracle_gqa_fwd.argtypes = [dp, dp, dp, dp, dp, L, L, L, L, L, I, F]
         lib.oracle_gqa_bwd.argtypes = [dp, dp, dp, dp, dp, dp, dp, L, L, L, L, L, I, F]
+        lib.oracle_rect_fwd.argtypes = [dp, dp, dp, dp, dp, L, L, L, L, L, L, I, F]
+        lib.oracle_rect_fwd.restype = ctypes.c_int
+        lib.oracle_rect_bwd.argtypes = [dp, dp, dp, dp, dp, dp, dp, L, L, L, L, L, L, I, F]
+        lib.oracle_rect_bwd.restype = ctypes.c_int
         lib.oracle_gemm.argtypes = [dp, dp, dp, L, L, L]
         lib.oracle_gemm.restype = ctypes.c_int
         lib.oracle_gemm_elements.argtypes = [dp, dp, lp, lp, L, dp, L, L, L]
@@ -156,6 +160,47 @@ def gqa_bwd(q, k, v, d_o, causal: bool, scale: float):
                                 B, Hq, Hkv, N, D, int(causal), float(scale))
     if rc:
         raise RuntimeError(f"oracle_gqa_bwd failed: {rc}")
+    return dq, dk, dv
+
+
+def _rect_dims(q, k, v, causal):
+    if q.ndim != 4 or k.ndim != 4 or k.shape != v.shape:
+        raise ValueError("q must be [B, Hq, Nq, D]; k, v [B, Hkv, Nk, D]")
+    B, Hq, Nq, D = q.shape
+    if k.shape[0] != B or k.shape[3] != D or Hq % k.shape[1]:
+        raise ValueError("k, v must be [B, Hkv, Nk, D] with Hkv dividing Hq")
+    if causal and Nq > k.shape[2]:
+        raise ValueError("the causal mask needs Nq <= Nk")
+    return B, Hq, k.shape[1], Nq, k.shape[2], D
+
+
+def rect_fwd(q, k, v, causal: bool, scale: float):
+    """Attention with Nq queries and Nk keys: q [B,Hq,Nq,D], k, v [B,Hkv,Nk,D] -> O [B,Hq,Nq,D],
+    LSE [B,Hq,Nq] (float64).  Causal: query i attends to keys j <= i + (Nk - Nq) (sequences
+    aligned at their ends; needs Nq <= Nk)."""
+    B, Hq, Hkv, Nq, Nk, D = _rect_dims(q, k, v, causal)
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v)
+    o = np.empty(q.shape, np.float64)
+    lse = np.empty(q.shape[:-1], np.float64)
+    rc = _load().oracle_rect_fwd(qp, kp, vp, _c(o)[1], _c(lse)[1], B, Hq, Hkv, Nq, Nk, D, int(causal), float(scale))
+    if rc:
+        raise RuntimeError(f"oracle_rect_fwd failed: {rc}")
+    return o, lse
+
+
+def rect_bwd(q, k, v, d_o, causal: bool, scale: float):
+    """dQ [B,Hq,Nq,D], dK, dV [B,Hkv,Nk,D] (float64) of rect_fwd for L = sum O * dO."""
+    B, Hq, Hkv, Nq, Nk, D = _rect_dims(q, k, v, causal)
+    if d_o.shape != q.shape:
+        raise ValueError("d_o must have q's shape")
+    q, qp = _c(q); k, kp = _c(k); v, vp = _c(v); d_o, dop = _c(d_o)
+    dq = np.empty(q.shape, np.float64)
+    dk = np.empty(k.shape, np.float64)
+    dv = np.empty(k.shape, np.float64)
+    rc = _load().oracle_rect_bwd(qp, kp, vp, dop, _c(dq)[1], _c(dk)[1], _c(dv)[1],
+                                 B, Hq, Hkv, Nq, Nk, D, int(causal), float(scale))
+    if rc:
+        raise RuntimeError(f"oracle_rect_bwd failed: {rc}")
     return dq, dk, dv
 
 
