@@ -159,6 +159,32 @@ int tk_attn_bwd_dq_gqa(const void* q, const void* k, const void* v, const void* 
                        int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream);
 
 /*
+ * Different numbers of queries and keys (cross attention, decoding against a longer key/value
+ * history).  The paper's listings take one sequence length, and its Appendix B.3 kernel guards
+ * only the query tail; the reading taken here: q has Nq rows per head, k and v have Nk rows, and
+ * with the causal mask the two sequences are aligned at their ENDS: query i attends to keys
+ * j <= i + (Nk - Nq), so the last query sees every key and Nq == Nk gives the calls above.
+ *
+ *   q, o, d_o, dq : bf16 [B, Hq, Nq, D]       k, v, dk, dv : bf16 [B, Hkv, Nk, D]
+ *   lse           : fp32 [B, Hq, Nq]
+ *   Nq, Nk >= 1, any values; heads grouped as in the _gqa calls (Hkv == Hq: plain multi-head).
+ *   workspace for tk_attn_bwd_rect: tk_attn_bwd_workspace_bytes(B, Hq, Nq, D) bytes.
+ * TK_ERR_BAD_DIM also covers causal != 0 with Nq > Nk (the first queries would see no key).
+ * Everything else (pointers, alignment, scale, stream, errors) as in the calls above.
+ */
+int tk_attn_fwd_rect(const void* q, const void* k, const void* v,
+                     void* o, float* lse,
+                     int B, int Hq, int Hkv, int Nq, int Nk, int D, int causal, float scale,
+                     void* stream);
+
+int tk_attn_bwd_rect(const void* q, const void* k, const void* v,
+                     const void* o, const void* d_o, const float* lse,
+                     void* dq, void* dk, void* dv,
+                     int B, int Hq, int Hkv, int Nq, int Nk, int D, int causal, float scale,
+                     void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/*
  * bf16 matrix multiply (the GEMM of the paper's appendix, second workload): C = A B with fp32
  * accumulation and one rounding to bf16.
  *

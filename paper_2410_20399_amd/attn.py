@@ -23,7 +23,7 @@ TK_ERR_LAUNCH = -6
 
 EXPORTS = ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
            "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_attn_fwd_gqa", "tk_attn_bwd_gqa", "tk_attn_bwd_dkdv_gqa",
-           "tk_attn_bwd_dq_gqa", "tk_rotary", "tk_gemm", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
+           "tk_attn_bwd_dq_gqa", "tk_attn_fwd_rect", "tk_attn_bwd_rect", "tk_rotary", "tk_gemm", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
 
 _lib = None
 
@@ -65,6 +65,10 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.tk_attn_bwd_dkdv_gqa.restype = i
     lib.tk_attn_bwd_dq_gqa.argtypes = [vp, vp, vp, vp, fp, fp, vp, i, i, i, i, i, i, f, vp]
     lib.tk_attn_bwd_dq_gqa.restype = i
+    lib.tk_attn_fwd_rect.argtypes = [vp, vp, vp, vp, fp, i, i, i, i, i, i, i, f, vp]
+    lib.tk_attn_fwd_rect.restype = i
+    lib.tk_attn_bwd_rect.argtypes = [vp, vp, vp, vp, vp, fp, vp, vp, vp, i, i, i, i, i, i, i, f, vp, sz, vp]
+    lib.tk_attn_bwd_rect.restype = i
     lib.tk_gemm.argtypes = [vp, vp, vp, i, i, i, vp]
     lib.tk_gemm.restype = i
     lib.tk_rotary.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
@@ -151,6 +155,18 @@ def tk_attn_bwd_gqa(q, k, v, o, d_o, lse, dq, dk, dv, B, Hq, Hkv, N, D, causal, 
     return load_library().tk_attn_bwd_gqa(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dq),
                                           _ptr(dk), _ptr(dv), B, Hq, Hkv, N, D, int(bool(causal)), float(scale),
                                           _ptr(workspace), int(workspace_bytes), _stream(stream))
+
+
+def tk_attn_fwd_rect(q, k, v, o, lse, B, Hq, Hkv, Nq, Nk, D, causal, scale, stream=None) -> int:
+    return load_library().tk_attn_fwd_rect(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, Hq, Hkv, Nq, Nk, D,
+                                           int(bool(causal)), float(scale), _stream(stream))
+
+
+def tk_attn_bwd_rect(q, k, v, o, d_o, lse, dq, dk, dv, B, Hq, Hkv, Nq, Nk, D, causal, scale, workspace,
+                     workspace_bytes, stream=None) -> int:
+    return load_library().tk_attn_bwd_rect(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dq),
+                                           _ptr(dk), _ptr(dv), B, Hq, Hkv, Nq, Nk, D, int(bool(causal)), float(scale),
+                                           _ptr(workspace), int(workspace_bytes), _stream(stream))
 
 
 def tk_attn_bwd_dkdv_gqa(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, N, D, causal, scale, stream=None) -> int:
@@ -267,6 +283,42 @@ def gqa_bwd(q, k, v, o, d_o, lse, causal: bool, scale: float, workspace=None, st
                          workspace, workspace.numel() * workspace.element_size(), stream)
     if rc != TK_OK:
         raise TkAttnError(rc, "tk_attn_bwd_gqa")
+    return dq, dk, dv
+
+
+def rect_fwd(q, k, v, causal: bool, scale: float, stream=None):
+    """Forward with Nq queries and Nk keys: q bf16 [B,Hq,Nq,D], k, v bf16 [B,Hkv,Nk,D].
+    Returns (o [B,Hq,Nq,D], lse [B,Hq,Nq]).  Causal: query i sees keys j <= i + (Nk - Nq)."""
+    _check_bf16("q", q)
+    B, Hq, Nq, D = q.shape
+    Hkv, Nk = k.shape[1], k.shape[2]
+    _check_bf16("k", k, (B, Hkv, Nk, D))
+    _check_bf16("v", v, (B, Hkv, Nk, D))
+    o = torch.empty_like(q)
+    lse = torch.empty((B, Hq, Nq), dtype=torch.float32, device=q.device)
+    rc = tk_attn_fwd_rect(q, k, v, o, lse, B, Hq, Hkv, Nq, Nk, D, causal, scale, stream)
+    if rc != TK_OK:
+        raise TkAttnError(rc, "tk_attn_fwd_rect")
+    return o, lse
+
+
+def rect_bwd(q, k, v, o, d_o, lse, causal: bool, scale: float, workspace=None, stream=None):
+    """Backward of rect_fwd. Returns (dq [B,Hq,Nq,D], dk, dv [B,Hkv,Nk,D]) bf16."""
+    _check_bf16("q", q)
+    B, Hq, Nq, D = q.shape
+    Hkv, Nk = k.shape[1], k.shape[2]
+    _check_bf16("k", k, (B, Hkv, Nk, D))
+    _check_bf16("v", v, (B, Hkv, Nk, D))
+    _check_bf16("o", o, q.shape)
+    _check_bf16("d_o", d_o, q.shape)
+    _check_f32("lse", lse, (B, Hq, Nq))
+    if workspace is None:
+        workspace = alloc_bwd_workspace(B, Hq, Nq, D, q.device)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    rc = tk_attn_bwd_rect(q, k, v, o, d_o, lse, dq, dk, dv, B, Hq, Hkv, Nq, Nk, D, causal, scale,
+                          workspace, workspace.numel() * workspace.element_size(), stream)
+    if rc != TK_OK:
+        raise TkAttnError(rc, "tk_attn_bwd_rect")
     return dq, dk, dv
 
 

@@ -110,13 +110,15 @@ template <int D> __device__ __forceinline__ int swz(int row) {
 // the query-block stream never stops: the loads issued during the last blocks of one key tile
 // already fetch the first blocks of the next, and the next tile's K, V fragments are requested
 // before the current tile's results are stored.
-// TAIL: N is not a multiple of 128 (the aligned case compiles without any of the tail code).
+// Nq queries, Nk keys.  TAIL: the general case (Nq != Nk, or a length that is not a multiple of
+// 128); the aligned square case compiles without any of the tail code.  Causal: query i sees keys
+// j <= i + (Nk - Nq), Nq <= Nk.
 template <int D, bool CAUSAL, bool TAIL>
 __global__ __launch_bounds__(256, 1)
 void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                           const bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
                           bf16* __restrict__ dK, bf16* __restrict__ dV,
-                          int N, int num_kv_tiles, int total_units, float scale, int hq, int hkv)
+                          int Nq, int Nk, int num_kv_tiles, int total_units, float scale, int hq, int hkv)
 {
     using S = DkdvShape<D>;
     __shared__ __attribute__((aligned(1024))) char ring[S::kStages * S::kStageBytes];
@@ -131,16 +133,30 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     const int ghalf = (lane >> 4) & 1;
     const float c = scale * kLog2e;
 
-    // Work unit: one key tile, or, when causal, the pair (u, last - u): tile u loops over
-    // (N - 128u)/32 query blocks, so every pair carries the same work and the static schedule is
-    // balanced.  A "pass" is one key tile; (vu, half) names the pass `half` of unit vu.
+    // Work unit: one key tile, or, when causal, the pair (u, last - u): tile u loops over the
+    // query blocks from its diagonal on, so the pairs carry (nearly) the same work and the static
+    // schedule is balanced.  A "pass" is one key tile; (vu, half) names the pass `half` of unit vu.
     // Grouped-query attention: a key/value head is shared by `group` consecutive query heads, and a
     // pass streams the query blocks of all of them, one head after the other, into the same dK, dV
     // accumulators.  bh below counts key/value heads.
     const int group = hq / hkv;
     const int units = CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles;
     auto q_head_row = [&](int bh) {         // first row of the first query head of key/value head bh
-        return (size_t)((bh / hkv) * hq + (bh % hkv) * group) * N;
+        return (size_t)((bh / hkv) * hq + (bh % hkv) * group) * Nq;
+    };
+    // The query blocks of a pass: blocks of 32 rows from pass_ibegin(kt) on, per query head of the
+    // group; an even count (the loops below take two blocks per trip), of which the first
+    // `n_masked` may touch the diagonal.  General case: the first query that sees a key of the tile
+    // is j0 - off, rounded down to a block boundary; rows past Nq are padding.
+    const int off = TAIL ? Nk - Nq : 0;
+    auto pass_ibegin = [&](int kt) {
+        if (!CAUSAL) return 0;
+        if (!TAIL) return kt * S::kTileKV;
+        const int first = kt * S::kTileKV - off;
+        return first > 0 ? first & ~(S::kTileQ - 1) : 0;
+    };
+    auto pass_nblocks = [&](int ibegin) {
+        return TAIL ? 2 * ((Nq - ibegin + 2 * S::kTileQ - 1) / (2 * S::kTileQ)) : (Nq - ibegin) / S::kTileQ;
     };
     auto pass_tile = [&](int vu, int half, int& bh, int& kt) {
         const int logical = xcd_remap(vu, total_units);
@@ -170,10 +186,9 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     // order the passes consume them.  Every call issues the same number of loads (the vmcnt waits
     // below count them); once the walk is exhausted it fetches the spare block again into a
     // stage nobody reads.
-    // N need not be a multiple of the tile sizes: the kernel works on the sequence padded to 128
-    // (n_pad).  Reads of rows >= N are redirected to row N-1; a query row >= N gets LSE = +inf, so
-    // its P and dS are exactly 0; key rows >= N are computed like any other and not stored.
-    const int n_pad = num_kv_tiles * S::kTileKV;
+    // The lengths need not be multiples of the tile sizes: the kernel works on padded sequences.
+    // Reads of rows past the end are redirected to the last row; a query row >= Nq gets LSE = +inf,
+    // so its P and dS are exactly 0; key rows >= Nk are computed like any other and not stored.
     int p_vu = blockIdx.x, p_half = 0, p_blk = 0, p_nblocks = 0, p_g = 0, p_ibegin = 0;
     size_t p_head_row = 0;                  // first row of the group's first query head of the producer's pass
     size_t spare_head_row = 0;
@@ -182,19 +197,19 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     auto producer_open = [&]() {            // set the cursor to the first block of pass (p_vu, p_half)
         int bh, kt;
         pass_tile(p_vu, p_half, bh, kt);
-        p_ibegin = CAUSAL ? kt * S::kTileKV : 0;
+        p_ibegin = pass_ibegin(kt);
         p_head_row = q_head_row(bh);
-        p_nblocks = (n_pad - p_ibegin) / S::kTileQ;
+        p_nblocks = pass_nblocks(p_ibegin);
         p_blk = 0;
         p_g = 0;
     };
     auto issue_next = [&]() {
         const bool live = p_vu < total_units;
-        const size_t head_row = live ? p_head_row + (size_t)p_g * N : spare_head_row;
+        const size_t head_row = live ? p_head_row + (size_t)p_g * Nq : spare_head_row;
         const int i0 = live ? p_ibegin + p_blk * S::kTileQ : spare_i0;      // first query of the block, within its head
         const size_t row = head_row + i0;
         char* base = ring + (p_count & (S::kStages - 1)) * S::kStageBytes;
-        if (!TAIL || i0 + S::kTileQ <= N) {
+        if (!TAIL || i0 + S::kTileQ <= Nq) {
 #pragma unroll
             for (int it = 0; it < S::kQLoads; it++)
                 load_global_to_lds16_untracked(Q + row * D + q_src[it], base + it * (S::kThreads * 16) + wave * 1024);
@@ -203,17 +218,17 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
                 load_global_to_lds16_untracked(dO + row * D + q_src[it],
                                                base + S::kQTileBytes + it * (S::kThreads * 16) + wave * 1024);
         } else {
-            // the block runs past the last query: rows >= N fetch row N-1 instead
+            // the block runs past the last query: rows >= Nq fetch row Nq-1 instead
 #pragma unroll
             for (int it = 0; it < S::kQLoads; it++) {
                 const int r = i0 + (it * S::kThreads + tid) / S::kChunksPerRow;
-                const int back = (r < N ? 0 : r - (N - 1)) * D;         // elements to step back
+                const int back = (r < Nq ? 0 : r - (Nq - 1)) * D;       // elements to step back
                 load_global_to_lds16_untracked(Q + row * D + q_src[it] - back, base + it * (S::kThreads * 16) + wave * 1024);
             }
 #pragma unroll
             for (int it = 0; it < S::kQLoads; it++) {
                 const int r = i0 + (it * S::kThreads + tid) / S::kChunksPerRow;
-                const int back = (r < N ? 0 : r - (N - 1)) * D;
+                const int back = (r < Nq ? 0 : r - (Nq - 1)) * D;
                 load_global_to_lds16_untracked(dO + row * D + q_src[it] - back,
                                                base + S::kQTileBytes + it * (S::kThreads * 16) + wave * 1024);
             }
@@ -221,8 +236,8 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         if (TAIL) {
             if (wave == 0) {   // lanes 0..31 fetch LSE of the block's 32 queries, lanes 32..63 their Delta
                 const int r = i0 + l32;
-                const float* src = (lane < 32) ? (r < N ? LSE + head_row + r : g_lse_pad)
-                                               : Delta + head_row + (r < N ? r : N - 1);
+                const float* src = (lane < 32) ? (r < Nq ? LSE + head_row + r : g_lse_pad)
+                                               : Delta + head_row + (r < Nq ? r : Nq - 1);
                 load_global_to_lds4_untracked(src, base + 2 * S::kQTileBytes);
             }
         } else if (wave == 0 && lane < 16) {   // 8 lanes fetch LSE[row..row+31], 8 lanes Delta[row..row+31], 16 bytes each
@@ -250,7 +265,7 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     bf16x8 kf[D / 16], vf[D / 16];          // K, V fragments of this wave's 32 keys (B operands of S = Q K^T and dP = dO V^T)
     auto load_kv = [&](int bh, int kt) {
         const int key = kt * S::kTileKV + wave * 32 + l32;
-        const size_t row = (size_t)bh * N + ((!TAIL || key < N) ? key : N - 1);
+        const size_t row = (size_t)bh * Nk + ((!TAIL || key < Nk) ? key : Nk - 1);
 #pragma unroll
         for (int kb = 0; kb < D / 16; kb++) {
             kf[kb] = *(const bf16x8*)(K + row * D + kb * 16 + h * 8);
@@ -275,12 +290,15 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     while (c_vu < total_units) {
     int bh, kt;
     pass_tile(c_vu, c_half, bh, kt);
-    const size_t head = (size_t)bh * N * D;        // of the key/value head
+    const size_t head = (size_t)bh * Nk * D;       // of the key/value head
     const int j0 = kt * S::kTileKV;
     const int jw0 = j0 + wave * 32;                // first key of this wave
     const int my_j = jw0 + l32;
-    const int i_begin = CAUSAL ? j0 : 0;
-    const int n_blocks = (n_pad - i_begin) / S::kTileQ;   // per query head of the group
+    const int i_begin = pass_ibegin(kt);
+    const int n_blocks = pass_nblocks(i_begin);           // per query head of the group
+    // blocks that may hold a masked (query, key) pair: rows below j0 + 127 - off, i.e. four blocks
+    // from i_begin when that is the tile's own first row, up to five when off is not a multiple of 32
+    const int n_masked = !CAUSAL ? 0 : !TAIL ? 4 : (n_blocks < 6 ? n_blocks : 6);
     spare_head_row = q_head_row(bh);
     spare_i0 = i_begin;
 
@@ -373,7 +391,7 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         if (decltype(masked)::value) {
 #pragma unroll
             for (int r = 0; r < 16; r++)
-                if (i0 + 8 * (r >> 2) + 4 * h + (r & 3) < my_j) s[r] = -INFINITY;
+                if (i0 + 8 * (r >> 2) + 4 * h + (r & 3) + off < my_j) s[r] = -INFINITY;
         }
 #pragma unroll
         for (int g = 0; g < 4; g++) {
@@ -414,14 +432,14 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // n_blocks is a multiple of 4; when causal, blocks 0..3 of every query head are the ones that
-    // touch the diagonal.  The deferred products run on across the heads of the group.
+    // n_blocks and n_masked are even; when causal, the first n_masked blocks of every query head are
+    // the ones that may touch the diagonal.  The deferred products run on across the heads of the group.
 #pragma unroll 1
     for (int g = 0; g < group; g++) {
         int blk = 0;
         if (CAUSAL) {
 #pragma unroll 1
-            for (; blk < 4; blk += 2) {
+            for (; blk < n_masked; blk += 2) {
                 step(std::true_type{}, blk, set_a, set_b);
                 step(std::true_type{}, blk + 1, set_b, set_a);
             }
@@ -468,7 +486,7 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
             const int row = i * kRowsPerStore + sub_row;
             const char* src = my_epi + row * S::kEpiPitch + col16 * 16;
             const bf16x4 lo = *(const bf16x4*)src, hi = *(const bf16x4*)(src + 8);
-            if (!TAIL || jw0 + row < N) *(bf16x8*)(dst + (size_t)row * D + col16 * 8) = concat(lo, hi);
+            if (!TAIL || jw0 + row < Nk) *(bf16x8*)(dst + (size_t)row * D + col16 * 8) = concat(lo, hi);
         }
     };
     store_tile(dk_acc, scale, dK + head + (size_t)jw0 * D);
@@ -480,10 +498,10 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
 template <int D, bool CAUSAL, bool TAIL>
 static hipError_t launch_dkdv_tt(const void* q, const void* k, const void* v, const void* d_o,
                                  const float* lse, const float* delta, void* dk, void* dv,
-                                 int B, int H, int Hkv, int N, float scale, hipStream_t stream)
+                                 int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
 {
     using S = DkdvShape<D>;
-    const int num_kv_tiles = (N + S::kTileKV - 1) / S::kTileKV;
+    const int num_kv_tiles = (Nk + S::kTileKV - 1) / S::kTileKV;
     const int total_units = B * Hkv * (CAUSAL ? (num_kv_tiles + 1) / 2 : num_kv_tiles);
     int cus = 0;
     hipError_t e = compute_unit_count(&cus);
@@ -491,28 +509,29 @@ static hipError_t launch_dkdv_tt(const void* q, const void* k, const void* v, co
     const int grid = total_units < cus ? total_units : cus;     // one resident workgroup per compute unit
     hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL, TAIL>), dim3(grid), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
-                       (bf16*)dk, (bf16*)dv, N, num_kv_tiles, total_units, scale, H, Hkv);
+                       (bf16*)dk, (bf16*)dv, Nq, Nk, num_kv_tiles, total_units, scale, H, Hkv);
     return hipGetLastError();
 }
 
 template <int D, bool CAUSAL>
 static hipError_t launch_dkdv_t(const void* q, const void* k, const void* v, const void* d_o,
                                 const float* lse, const float* delta, void* dk, void* dv,
-                                int B, int H, int Hkv, int N, float scale, hipStream_t stream)
+                                int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
 {
     using S = DkdvShape<D>;
-    return N % S::kTileKV ? launch_dkdv_tt<D, CAUSAL, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, N, scale, stream)
-                          : launch_dkdv_tt<D, CAUSAL, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, N, scale, stream);
+    return (Nq != Nk || Nk % S::kTileKV)
+               ? launch_dkdv_tt<D, CAUSAL, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream)
+               : launch_dkdv_tt<D, CAUSAL, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream);
 }
 
 hipError_t launch_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
                                 const float* lse, const float* delta, void* dk, void* dv,
-                                int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream)
+                                int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream)
 {
-    if (D == 128) return causal ? launch_dkdv_t<128, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, N, scale, stream)
-                                : launch_dkdv_t<128, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, N, scale, stream);
-    return causal ? launch_dkdv_t<64, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, N, scale, stream)
-                  : launch_dkdv_t<64, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, N, scale, stream);
+    if (D == 128) return causal ? launch_dkdv_t<128, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream)
+                                : launch_dkdv_t<128, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream);
+    return causal ? launch_dkdv_t<64, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream)
+                  : launch_dkdv_t<64, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -535,7 +554,7 @@ template <int D, bool CAUSAL, bool TAIL>
 __global__ __launch_bounds__(256, 2)
 void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                         const bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
-                        bf16* __restrict__ dQ, int N, int num_q_tiles, int total_wg, float scale, int hq, int hkv)
+                        bf16* __restrict__ dQ, int Nq, int Nk, int num_q_tiles, int total_wg, float scale, int hq, int hkv)
 {
     using S = DqShape<D>;
     __shared__ __attribute__((aligned(1024))) char stage0[S::kStageBytes];
@@ -547,15 +566,17 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
     const int l32 = lane & 31;
     const int h = lane >> 5;
 
-    // Work unit: one query tile, or, when causal, the pair (last - u, u): tile t streams t+1 blocks
-    // of 128 keys, so every pair carries the same work and the launch is balanced.
+    // Work unit: one query tile, or, when causal, the pair (last - u, u): tile t streams the keys up
+    // to its diagonal, so the pairs carry (nearly) the same work and the launch is balanced.
+    // Nq queries, Nk keys; TAIL and the causal alignment as in the kernels above.
     const int units = CAUSAL ? (num_q_tiles + 1) / 2 : num_q_tiles;
     const int logical = xcd_remap(blockIdx.x, total_wg);
     const int bh = logical / units;
     const int unit = logical % units;
     // grouped-query attention: query head h of a batch entry reads key/value head h / (hq / hkv)
-    const size_t head = (size_t)bh * N * D;
-    const size_t kv_head = (size_t)((bh / hq) * hkv + (bh % hq) / (hq / hkv)) * N * D;
+    const size_t head = (size_t)bh * Nq * D;
+    const size_t kv_head = (size_t)((bh / hq) * hkv + (bh % hq) / (hq / hkv)) * Nk * D;
+    const int off = TAIL ? Nk - Nq : 0;          // causal: query i sees keys <= i + off
     const bf16* Kh = K + kv_head;
     const bf16* Vh = V + kv_head;
 #pragma unroll 1
@@ -564,9 +585,10 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
     if (pass == 1 && qt == num_q_tiles - 1 - unit) break;   // odd tile count: the middle tile has no partner
     const int q0 = qt * S::kTileQ + wave * 32;
     const int my_q = q0 + l32;
-    // N need not be a multiple of the tile sizes: the kernel works on the sequence padded to 128,
-    // reads of rows >= N are redirected to row N-1, keys >= N are masked, rows >= N are not stored.
-    const int my_q_ld = (!TAIL || my_q < N) ? my_q : N - 1;
+    // The lengths need not be multiples of the tile sizes: the kernel works on padded sequences,
+    // reads of rows past the end are redirected to the last row, keys >= Nk are masked, query rows
+    // >= Nq are not stored.
+    const int my_q_ld = (!TAIL || my_q < Nq) ? my_q : Nq - 1;
     const float c = scale * kLog2e;
 
     // ---- Q_i, dO_i fragments (B operands of S^T = K Q^T and dP^T = V dO^T) and the row statistics
@@ -576,8 +598,8 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
         qf[kb] = *(const bf16x8*)(Q + head + (size_t)my_q_ld * D + kb * 16 + h * 8);
         dof[kb] = *(const bf16x8*)(dO + head + (size_t)my_q_ld * D + kb * 16 + h * 8);
     }
-    const float lse2 = LSE[(size_t)bh * N + my_q_ld] * kLog2e;
-    const float delta = Delta[(size_t)bh * N + my_q_ld];
+    const float lse2 = LSE[(size_t)bh * Nq + my_q_ld] * kLog2e;
+    const float delta = Delta[(size_t)bh * Nq + my_q_ld];
 
     // ---- direct-to-LDS tile loads (same slot arithmetic as the forward kernel)
     int kv_src[S::kLoadsPerTile];
@@ -591,7 +613,7 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
         const int j0 = tile * S::kTileKV;
         const bf16* kt = Kh + (size_t)j0 * D;
         const bf16* vt = Vh + (size_t)j0 * D;
-        if (!TAIL || j0 + S::kTileKV <= N) {
+        if (!TAIL || j0 + S::kTileKV <= Nk) {
 #pragma unroll
             for (int it = 0; it < S::kLoadsPerTile; it++)
                 load_global_to_lds16(kt + kv_src[it], base + wave * 1024 + it * (S::kThreads * 16));
@@ -599,11 +621,11 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
             for (int it = 0; it < S::kLoadsPerTile; it++)
                 load_global_to_lds16(vt + kv_src[it], base + S::kTileBytes + wave * 1024 + it * (S::kThreads * 16));
         } else {
-            // the tile runs past the last key: rows >= N fetch row N-1 instead (they are masked later)
+            // the tile runs past the last key: rows >= Nk fetch row Nk-1 instead (they are masked later)
 #pragma unroll
             for (int it = 0; it < S::kLoadsPerTile; it++) {
                 const int row = j0 + (it * S::kThreads + tid) / S::kChunksPerRow;
-                const int back = (row < N ? 0 : row - (N - 1)) * D;     // elements to step back
+                const int back = (row < Nk ? 0 : row - (Nk - 1)) * D;   // elements to step back
                 load_global_to_lds16(kt + kv_src[it] - back, base + wave * 1024 + it * (S::kThreads * 16));
                 load_global_to_lds16(vt + kv_src[it] - back, base + S::kTileBytes + wave * 1024 + it * (S::kThreads * 16));
             }
@@ -627,10 +649,10 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
 
     auto compute_tile = [&](const char* ks, int tile) {
         const int j0 = tile * S::kTileKV;
-        if (CAUSAL && j0 > q0 + 31) return;          // every key of the tile is masked for this wave
+        if (CAUSAL && j0 > q0 + 31 + off) return;    // every key of the tile is masked for this wave
         const char* vs = ks + S::kTileBytes;
         // the tile crosses this wave's diagonal, or runs past the last key
-        const bool diag = (CAUSAL && (j0 + S::kTileKV - 1 > q0)) || (TAIL && j0 + S::kTileKV > N);
+        const bool diag = (CAUSAL && (j0 + S::kTileKV - 1 > q0 + off)) || (TAIL && j0 + S::kTileKV > Nk);
         // The tile is processed in two halves of 32 keys, so that only one half's S^T / dP^T
         // accumulators are live at a time.
 #pragma unroll
@@ -651,7 +673,7 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int key = j0 + 32 * b + 8 * (r >> 2) + 4 * h + (r & 3);
-                    if ((CAUSAL && key > my_q) || (TAIL && key >= N)) s[r] = -INFINITY;
+                    if ((CAUSAL && key > my_q + off) || (TAIL && key >= Nk)) s[r] = -INFINITY;
                 }
             }
 #pragma unroll
@@ -677,8 +699,15 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
         }
     };
 
-    // key tiles of the sequence padded to the query tile size; even
-    const int n_tiles = (CAUSAL ? qt * S::kTileQ + S::kTileQ : num_q_tiles * S::kTileQ) / S::kTileKV;
+    // key tiles this workgroup visits: an even count that covers every key visible to its last query
+    int n_tiles;
+    if (!TAIL) {
+        n_tiles = (CAUSAL ? qt * S::kTileQ + S::kTileQ : num_q_tiles * S::kTileQ) / S::kTileKV;
+    } else {
+        int n_keys = Nk;
+        if (CAUSAL && qt * S::kTileQ + S::kTileQ + off < n_keys) n_keys = qt * S::kTileQ + S::kTileQ + off;
+        n_tiles = 2 * ((n_keys + 2 * S::kTileKV - 1) / (2 * S::kTileKV));
+    }
     issue_tile(stage0, 0);
     wait_vmcnt<0>();
     __syncthreads();
@@ -694,7 +723,7 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
     }
 
     // ---- epilogue: dQ = scale * acc; lane <-> query, register r of block db <-> column 32db + 8*(r/4) + 4h + r%4
-    if (!TAIL || my_q < N) {
+    if (!TAIL || my_q < Nq) {
         bf16* dQr = dQ + head + (size_t)my_q * D;
 #pragma unroll
         for (int db = 0; db < D / 32; db++)
@@ -711,35 +740,36 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
 template <int D, bool CAUSAL, bool TAIL>
 static hipError_t launch_dq_tt(const void* q, const void* k, const void* v, const void* d_o,
                                const float* lse, const float* delta, void* dq,
-                               int B, int H, int Hkv, int N, float scale, hipStream_t stream)
+                               int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
 {
     using S = DqShape<D>;
-    const int num_q_tiles = (N + S::kTileQ - 1) / S::kTileQ;
+    const int num_q_tiles = (Nq + S::kTileQ - 1) / S::kTileQ;
     const int total = B * H * (CAUSAL ? (num_q_tiles + 1) / 2 : num_q_tiles);
     hipLaunchKernelGGL((attn_bwd_dq_kernel<D, CAUSAL, TAIL>), dim3(total), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
-                       (bf16*)dq, N, num_q_tiles, total, scale, H, Hkv);
+                       (bf16*)dq, Nq, Nk, num_q_tiles, total, scale, H, Hkv);
     return hipGetLastError();
 }
 
 template <int D, bool CAUSAL>
 static hipError_t launch_dq_t(const void* q, const void* k, const void* v, const void* d_o,
                               const float* lse, const float* delta, void* dq,
-                              int B, int H, int Hkv, int N, float scale, hipStream_t stream)
+                              int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
 {
     using S = DqShape<D>;
-    return N % S::kTileQ ? launch_dq_tt<D, CAUSAL, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, N, scale, stream)
-                         : launch_dq_tt<D, CAUSAL, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, N, scale, stream);
+    return (Nq != Nk || Nq % S::kTileQ)
+               ? launch_dq_tt<D, CAUSAL, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream)
+               : launch_dq_tt<D, CAUSAL, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream);
 }
 
 hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
                               const float* lse, const float* delta, void* dq,
-                              int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream)
+                              int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream)
 {
-    if (D == 128) return causal ? launch_dq_t<128, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, N, scale, stream)
-                                : launch_dq_t<128, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, N, scale, stream);
-    return causal ? launch_dq_t<64, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, N, scale, stream)
-                  : launch_dq_t<64, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, N, scale, stream);
+    if (D == 128) return causal ? launch_dq_t<128, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream)
+                                : launch_dq_t<128, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream);
+    return causal ? launch_dq_t<64, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream)
+                  : launch_dq_t<64, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream);
 }
 
 }  // namespace tk

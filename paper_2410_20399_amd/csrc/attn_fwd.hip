@@ -41,12 +41,15 @@ template <int D> __device__ __forceinline__ int swizzle_v(int row) {
     return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
 }
 
-// TAIL: N is not a multiple of 128 (the aligned case compiles without any of the tail code).
+// Nq queries, Nk keys.  TAIL: the general case (Nq != Nk, or a length that is not a multiple of
+// 128); the aligned square case compiles without any of the tail code.  With the causal mask the
+// sequences are aligned at their ends: query i sees keys j <= i + (Nk - Nq); the host has checked
+// Nq <= Nk for that case, so every query sees key 0.
 template <int D, bool CAUSAL, bool TAIL>
 __global__ __launch_bounds__(256, 2)
 void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                      bf16* __restrict__ O, float* __restrict__ LSE,
-                     int N, int num_q_tiles, int total_wg, float scale, int hq, int hkv)
+                     int Nq, int Nk, int num_q_tiles, int total_wg, float scale, int hq, int hkv)
 {
     using S = FwdShape<D>;
     // One array per ring stage: distinct LDS objects let the compiler see that reads of the stage
@@ -68,16 +71,18 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
     if (CAUSAL) qt = num_q_tiles - 1 - qt;
 
     // grouped-query attention: query head h of a batch entry reads key/value head h / (hq / hkv)
-    const size_t head = (size_t)bh * N * D;
-    const size_t kv_head = (size_t)((bh / hq) * hkv + (bh % hq) / (hq / hkv)) * N * D;
+    const size_t head = (size_t)bh * Nq * D;
+    const size_t kv_head = (size_t)((bh / hq) * hkv + (bh % hq) / (hq / hkv)) * Nk * D;
     const bf16* Qh = Q + head;
     const bf16* Kh = K + kv_head;
     const bf16* Vh = V + kv_head;
     const int q0 = qt * S::kTileQ + wave * 32;   // first query row of this wave
     const int my_q = q0 + l32;
-    // N need not be a multiple of the tile sizes: the kernel works on the sequence padded to 128,
-    // reads of rows >= N are redirected to row N-1, keys >= N are masked, rows >= N are not stored.
-    const int my_q_ld = (!TAIL || my_q < N) ? my_q : N - 1;
+    // The lengths need not be multiples of the tile sizes: the kernel works on padded sequences,
+    // reads of rows past the end are redirected to the last row, keys >= Nk are masked, query rows
+    // >= Nq are not stored.
+    const int my_q_ld = (!TAIL || my_q < Nq) ? my_q : Nq - 1;
+    const int off = TAIL ? Nk - Nq : 0;          // causal: query i sees keys <= i + off
 
     const float c = scale * kLog2e;              // base-2 temperature
 
@@ -102,7 +107,7 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
         const bf16* kt = Kh + (size_t)j0 * D;
         const bf16* vt = Vh + (size_t)j0 * D;
         char* base = (stage ? smem1 : smem0) + wave * 1024;
-        if (!TAIL || j0 + S::kTileKV <= N) {
+        if (!TAIL || j0 + S::kTileKV <= Nk) {
 #pragma unroll
             for (int it = 0; it < S::kLoadsPerTile; it++)
                 load_global_to_lds16(kt + k_src[it], base + it * (S::kThreads * 16));
@@ -110,17 +115,17 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
             for (int it = 0; it < S::kLoadsPerTile; it++)
                 load_global_to_lds16(vt + v_src[it], base + S::kTileBytes + it * (S::kThreads * 16));
         } else {
-            // the tile runs past the last key: rows >= N fetch row N-1 instead (they are masked later)
+            // the tile runs past the last key: rows >= Nk fetch row Nk-1 instead (they are masked later)
 #pragma unroll
             for (int it = 0; it < S::kLoadsPerTile; it++) {
                 const int row = j0 + (it * S::kThreads + tid) / S::kChunksPerRow;
-                const int back = (row < N ? 0 : row - (N - 1)) * D;     // elements to step back
+                const int back = (row < Nk ? 0 : row - (Nk - 1)) * D;     // elements to step back
                 load_global_to_lds16(kt + k_src[it] - back, base + it * (S::kThreads * 16));
             }
 #pragma unroll
             for (int it = 0; it < S::kLoadsPerTile; it++) {
                 const int row = j0 + (it * S::kThreads + tid) / S::kChunksPerRow;
-                const int back = (row < N ? 0 : row - (N - 1)) * D;
+                const int back = (row < Nk ? 0 : row - (Nk - 1)) * D;
                 load_global_to_lds16(vt + v_src[it] - back, base + S::kTileBytes + it * (S::kThreads * 16));
             }
         }
@@ -147,7 +152,7 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
 
     auto compute_tile = [&](int stage, int tile) {
         const int j0 = tile * S::kTileKV;
-        if (CAUSAL && j0 > q0 + 31) return;          // every key of the tile is masked for this wave
+        if (CAUSAL && j0 > q0 + 31 + off) return;    // every key of the tile is masked for this wave
         const char* ks = stage ? smem1 : smem0;
         const char* vs = ks + S::kTileBytes;
 
@@ -164,13 +169,13 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
             }
         }
         // tile crosses the diagonal for some row of this wave, or runs past the last key
-        if ((CAUSAL && j0 + S::kTileKV - 1 > q0) || (TAIL && j0 + S::kTileKV > N)) {
+        if ((CAUSAL && j0 + S::kTileKV - 1 > q0 + off) || (TAIL && j0 + S::kTileKV > Nk)) {
 #pragma unroll
             for (int b = 0; b < 2; b++)
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     int key = j0 + 32 * b + 8 * (r >> 2) + 4 * h + (r & 3);
-                    if ((CAUSAL && key > my_q) || (TAIL && key >= N)) s[b][r] = -INFINITY;
+                    if ((CAUSAL && key > my_q + off) || (TAIL && key >= Nk)) s[b][r] = -INFINITY;
                 }
         }
         // running max
@@ -229,8 +234,15 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
         }
     };
 
-    // key tiles of the sequence padded to the query tile size; even
-    const int n_tiles = (CAUSAL ? qt * S::kTileQ + S::kTileQ : num_q_tiles * S::kTileQ) / S::kTileKV;
+    // key tiles this workgroup visits: an even count that covers every key visible to its last query
+    int n_tiles;
+    if (!TAIL) {
+        n_tiles = (CAUSAL ? qt * S::kTileQ + S::kTileQ : num_q_tiles * S::kTileQ) / S::kTileKV;
+    } else {
+        int n_keys = Nk;
+        if (CAUSAL && qt * S::kTileQ + S::kTileQ + off < n_keys) n_keys = qt * S::kTileQ + S::kTileQ + off;
+        n_tiles = 2 * ((n_keys + 2 * S::kTileKV - 1) / (2 * S::kTileKV));
+    }
 
     issue_tile(0, 0);
     wait_vmcnt<0>();
@@ -249,7 +261,7 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
     // ---- epilogue
     const float l_tot = half_sum(l_run);
     const float inv = 1.0f / l_tot;
-    if (!TAIL || my_q < N) {
+    if (!TAIL || my_q < Nq) {
         bf16* Oh = O + head + (size_t)my_q * D;
 #pragma unroll
         for (int db = 0; db < D / 32; db++)
@@ -259,40 +271,40 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
                 bf16x2 b = cvt2(o_acc[db][4 * g + 2] * inv, o_acc[db][4 * g + 3] * inv);
                 *(bf16x4*)(Oh + 32 * db + 8 * g + 4 * h) = __builtin_shufflevector(a, b, 0, 1, 2, 3);
             }
-        if (h == 0) LSE[(size_t)bh * N + my_q] = m_run * scale + __builtin_logf(l_tot);
+        if (h == 0) LSE[(size_t)bh * Nq + my_q] = m_run * scale + __builtin_logf(l_tot);
     }
 }
 
 template <int D, bool CAUSAL, bool TAIL>
 static hipError_t launch_fwd_tt(const void* q, const void* k, const void* v, void* o, float* lse,
-                                int B, int H, int Hkv, int N, float scale, hipStream_t stream)
+                                int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
 {
     using S = FwdShape<D>;
     auto kern = attn_fwd_kernel<D, CAUSAL, TAIL>;
-    const int num_q_tiles = (N + S::kTileQ - 1) / S::kTileQ;
+    const int num_q_tiles = (Nq + S::kTileQ - 1) / S::kTileQ;
     const int total = B * H * num_q_tiles;
     hipLaunchKernelGGL(kern, dim3(total), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, lse,
-                       N, num_q_tiles, total, scale, H, Hkv);
+                       Nq, Nk, num_q_tiles, total, scale, H, Hkv);
     return hipGetLastError();
 }
 
 template <int D, bool CAUSAL>
 static hipError_t launch_fwd_t(const void* q, const void* k, const void* v, void* o, float* lse,
-                               int B, int H, int Hkv, int N, float scale, hipStream_t stream)
+                               int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
 {
     using S = FwdShape<D>;
-    return N % S::kTileQ ? launch_fwd_tt<D, CAUSAL, true>(q, k, v, o, lse, B, H, Hkv, N, scale, stream)
-                         : launch_fwd_tt<D, CAUSAL, false>(q, k, v, o, lse, B, H, Hkv, N, scale, stream);
+    return (Nq != Nk || Nq % S::kTileQ) ? launch_fwd_tt<D, CAUSAL, true>(q, k, v, o, lse, B, H, Hkv, Nq, Nk, scale, stream)
+                                        : launch_fwd_tt<D, CAUSAL, false>(q, k, v, o, lse, B, H, Hkv, Nq, Nk, scale, stream);
 }
 
 hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
-                           int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream)
+                           int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream)
 {
-    if (D == 128) return causal ? launch_fwd_t<128, true>(q, k, v, o, lse, B, H, Hkv, N, scale, stream)
-                                : launch_fwd_t<128, false>(q, k, v, o, lse, B, H, Hkv, N, scale, stream);
-    return causal ? launch_fwd_t<64, true>(q, k, v, o, lse, B, H, Hkv, N, scale, stream)
-                  : launch_fwd_t<64, false>(q, k, v, o, lse, B, H, Hkv, N, scale, stream);
+    if (D == 128) return causal ? launch_fwd_t<128, true>(q, k, v, o, lse, B, H, Hkv, Nq, Nk, scale, stream)
+                                : launch_fwd_t<128, false>(q, k, v, o, lse, B, H, Hkv, Nq, Nk, scale, stream);
+    return causal ? launch_fwd_t<64, true>(q, k, v, o, lse, B, H, Hkv, Nq, Nk, scale, stream)
+                  : launch_fwd_t<64, false>(q, k, v, o, lse, B, H, Hkv, Nq, Nk, scale, stream);
 }
 
 }  // namespace tk

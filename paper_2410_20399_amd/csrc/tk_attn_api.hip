@@ -32,6 +32,15 @@ size_t delta_bytes(int B, int H, int N)
     return (b + 255) & ~(size_t)255;
 }
 
+// query and key lengths of one call; the causal mask aligns the sequences at their ends and needs Nq <= Nk
+int check_lengths(int B, int H, int Nq, int Nk, int D, int causal)
+{
+    if (int rc = check_shape(B, H, Nq, D)) return rc;
+    if (int rc = check_shape(B, H, Nk, D)) return rc;
+    if (causal && Nq > Nk) return TK_ERR_BAD_DIM;
+    return TK_OK;
+}
+
 int check_heads(int H, int Hkv)
 {
     return (Hkv >= 1 && Hkv <= H && H % Hkv == 0) ? TK_OK : TK_ERR_BAD_DIM;
@@ -41,16 +50,22 @@ int check_heads(int H, int Hkv)
 
 extern "C" {
 
-int tk_attn_fwd_gqa(const void* q, const void* k, const void* v, void* o, float* lse,
-                    int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream)
+int tk_attn_fwd_rect(const void* q, const void* k, const void* v, void* o, float* lse,
+                     int B, int Hq, int Hkv, int Nq, int Nk, int D, int causal, float scale, void* stream)
 {
     if (!q || !k || !v || !o || !lse) return TK_ERR_NULL_PTR;
-    if (int rc = check_shape(B, Hq, N, D)) return rc;
+    if (int rc = check_lengths(B, Hq, Nq, Nk, D, causal)) return rc;
     if (int rc = check_heads(Hq, Hkv)) return rc;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return TK_ERR_MISALIGNED;
     if (int rc = check_scale(scale)) return rc;
-    hipError_t e = tk::launch_attn_fwd(q, k, v, o, lse, B, Hq, Hkv, N, D, causal != 0, scale, (hipStream_t)stream);
+    hipError_t e = tk::launch_attn_fwd(q, k, v, o, lse, B, Hq, Hkv, Nq, Nk, D, causal != 0, scale, (hipStream_t)stream);
     return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
+int tk_attn_fwd_gqa(const void* q, const void* k, const void* v, void* o, float* lse,
+                    int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream)
+{
+    return tk_attn_fwd_rect(q, k, v, o, lse, B, Hq, Hkv, N, N, D, causal, scale, stream);
 }
 
 int tk_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
@@ -85,7 +100,7 @@ int tk_attn_bwd_dkdv_gqa(const void* q, const void* k, const void* v, const void
         !aligned16(delta) || !aligned16(dk) || !aligned16(dv))
         return TK_ERR_MISALIGNED;
     if (int rc = check_scale(scale)) return rc;
-    hipError_t e = tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, N, D, causal != 0, scale,
+    hipError_t e = tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, N, N, D, causal != 0, scale,
                                             (hipStream_t)stream);
     return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
 }
@@ -108,7 +123,7 @@ int tk_attn_bwd_dq_gqa(const void* q, const void* k, const void* v, const void* 
         !aligned16(delta) || !aligned16(dq))
         return TK_ERR_MISALIGNED;
     if (int rc = check_scale(scale)) return rc;
-    hipError_t e = tk::launch_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, Hq, Hkv, N, D, causal != 0, scale,
+    hipError_t e = tk::launch_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, Hq, Hkv, N, N, D, causal != 0, scale,
                                           (hipStream_t)stream);
     return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
 }
@@ -120,31 +135,40 @@ int tk_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
     return tk_attn_bwd_dq_gqa(q, k, v, d_o, lse, delta, dq, B, H, H, N, D, causal, scale, stream);
 }
 
-int tk_attn_bwd_gqa(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse,
-                    void* dq, void* dk, void* dv,
-                    int B, int Hq, int Hkv, int N, int D, int causal, float scale,
-                    void* workspace, size_t workspace_bytes, void* stream)
+int tk_attn_bwd_rect(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse,
+                     void* dq, void* dk, void* dv,
+                     int B, int Hq, int Hkv, int Nq, int Nk, int D, int causal, float scale,
+                     void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return TK_ERR_NULL_PTR;
-    if (int rc = check_shape(B, Hq, N, D)) return rc;
+    if (int rc = check_lengths(B, Hq, Nq, Nk, D, causal)) return rc;
     if (int rc = check_heads(Hq, Hkv)) return rc;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(lse) ||
         !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
         return TK_ERR_MISALIGNED;
     if (int rc = check_scale(scale)) return rc;
-    if (workspace_bytes < tk_attn_bwd_workspace_bytes(B, Hq, N, D)) return TK_ERR_WORKSPACE_TOO_SMALL;
+    if (workspace_bytes < tk_attn_bwd_workspace_bytes(B, Hq, Nq, D)) return TK_ERR_WORKSPACE_TOO_SMALL;
 
     hipStream_t s = (hipStream_t)stream;
     float* delta = (float*)workspace;
     // 1. Delta = rowsum(dO * O), per query head
-    if (tk::launch_attn_bwd_delta(o, d_o, delta, B, Hq, N, D, s) != hipSuccess) return TK_ERR_LAUNCH;
+    if (tk::launch_attn_bwd_delta(o, d_o, delta, B, Hq, Nq, D, s) != hipSuccess) return TK_ERR_LAUNCH;
     // 2. dK, dV per key tile of every key/value head
-    if (tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, N, D, causal != 0, scale, s) != hipSuccess)
+    if (tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, Nq, Nk, D, causal != 0, scale, s) != hipSuccess)
         return TK_ERR_LAUNCH;
     // 3. dQ per query tile
-    if (tk::launch_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, Hq, Hkv, N, D, causal != 0, scale, s) != hipSuccess)
+    if (tk::launch_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, Hq, Hkv, Nq, Nk, D, causal != 0, scale, s) != hipSuccess)
         return TK_ERR_LAUNCH;
     return TK_OK;
+}
+
+int tk_attn_bwd_gqa(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse,
+                    void* dq, void* dk, void* dv,
+                    int B, int Hq, int Hkv, int N, int D, int causal, float scale,
+                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return tk_attn_bwd_rect(q, k, v, o, d_o, lse, dq, dk, dv, B, Hq, Hkv, N, N, D, causal, scale,
+                            workspace, workspace_bytes, stream);
 }
 
 int tk_attn_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse,
@@ -190,7 +214,7 @@ const char* tk_status_string(int status)
     switch (status) {
         case TK_OK: return "ok";
         case TK_ERR_NULL_PTR: return "null pointer";
-        case TK_ERR_BAD_DIM: return "unsupported shape (D must be 64 or 128; B, H, N >= 1; Hkv must divide Hq)";
+        case TK_ERR_BAD_DIM: return "unsupported shape (D must be 64 or 128; B, H, N >= 1; Hkv must divide Hq; causal needs Nq <= Nk)";
         case TK_ERR_MISALIGNED: return "pointer not 16-byte aligned";
         case TK_ERR_BAD_SCALE: return "scale must be finite and > 0";
         case TK_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";

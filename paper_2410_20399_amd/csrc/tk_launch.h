@@ -14,9 +14,10 @@ inline hipError_t compute_unit_count(int* cus) {
 }
 
 // H query heads share Hkv key/value heads in groups of H / Hkv consecutive heads (Hkv == H: plain
-// multi-head attention).  q, o, d_o, dq: [B,H,N,D]; k, v, dk, dv: [B,Hkv,N,D]; lse, delta: [B,H,N].
+// multi-head attention); Nq queries, Nk keys per head (causal: aligned at their ends, Nq <= Nk).
+// q, o, d_o, dq: [B,H,Nq,D]; k, v, dk, dv: [B,Hkv,Nk,D]; lse, delta: [B,H,Nq].
 hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
-                           int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream);
+                           int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream);
 
 // Delta_i = sum_d dO_id O_id
 hipError_t launch_attn_bwd_delta(const void* o, const void* d_o, float* delta,
@@ -25,12 +26,12 @@ hipError_t launch_attn_bwd_delta(const void* o, const void* d_o, float* delta,
 // dK, dV (key-tile parallel)
 hipError_t launch_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
                                 const float* lse, const float* delta, void* dk, void* dv,
-                                int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream);
+                                int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream);
 
 // dQ (query-tile parallel)
 hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
                               const float* lse, const float* delta, void* dq,
-                              int B, int H, int Hkv, int N, int D, int causal, float scale, hipStream_t stream);
+                              int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream);
 
 // bf16 matrix multiply C = A B: A [M,K], B [K,N], C [M,N] row-major; M, N multiples of 256, K of 64
 hipError_t launch_gemm(const void* a, const void* b, void* c, int M, int N, int K, hipStream_t stream);

@@ -145,6 +145,34 @@ def test_gqa_entries_reject_bad_arguments(lib):
     assert lib.tk_attn_bwd_gqa(P, P, P, P, P, P, P, P, None, 1, 4, 2, 128, 64, 0, f(0.125), P, sz(need), None) == a.TK_ERR_NULL_PTR
 
 
+def test_rect_entries_reject_bad_arguments(lib):
+    from paper_2410_20399_amd import attn as a
+    f = ctypes.c_float
+    sz = ctypes.c_size_t
+
+    def fwd_rect(*, q=P, Hq=2, Hkv=1, Nq=5, Nk=300, D=64, causal=1, scale=0.125):
+        return lib.tk_attn_fwd_rect(q, P, P, P, P, 1, Hq, Hkv, Nq, Nk, D, causal, f(scale), None)
+
+    def bwd_rect(*, dk=P, Hq=2, Hkv=1, Nq=5, Nk=300, D=64, causal=1, scale=0.125, ws=P, ws_bytes=1 << 30):
+        return lib.tk_attn_bwd_rect(P, P, P, P, P, P, P, dk, P, 1, Hq, Hkv, Nq, Nk, D, causal, f(scale), ws, sz(ws_bytes), None)
+
+    for fn in (fwd_rect, bwd_rect):
+        assert fn(Nq=0) == a.TK_ERR_BAD_DIM
+        assert fn(Nk=0) == a.TK_ERR_BAD_DIM
+        assert fn(Nq=301, Nk=300, causal=1) == a.TK_ERR_BAD_DIM      # causal needs Nq <= Nk
+        assert fn(D=96) == a.TK_ERR_BAD_DIM
+        assert fn(Hq=3, Hkv=2) == a.TK_ERR_BAD_DIM
+        assert fn(scale=0.0) == a.TK_ERR_BAD_SCALE
+    assert fwd_rect(q=None) == a.TK_ERR_NULL_PTR
+    assert fwd_rect(q=ODD) == a.TK_ERR_MISALIGNED
+    assert bwd_rect(dk=None) == a.TK_ERR_NULL_PTR
+    assert bwd_rect(dk=ODD) == a.TK_ERR_MISALIGNED
+    assert bwd_rect(ws=None) == a.TK_ERR_NULL_PTR
+    need = lib.tk_attn_bwd_workspace_bytes(1, 2, 5, 64)       # sized by the QUERY length
+    assert need == 256
+    assert bwd_rect(ws_bytes=need - 1) == a.TK_ERR_WORKSPACE_TOO_SMALL
+
+
 def test_gemm_rejects_bad_arguments(lib):
     from paper_2410_20399_amd import attn as a
     for i in range(3):
