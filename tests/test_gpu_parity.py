@@ -247,3 +247,34 @@ def test_runs_on_side_stream_and_reuses_workspace(attn):
     for g in (g1, g2):
         for t, r in zip(g, (rq, rk, rv)):
             assert relf(f64(t.cpu()), r) <= GRAD_RELF
+
+
+def test_tensors_beyond_two_to_the_31_elements(attn):
+    """Every tensor holds more than 2^31 elements (over 4 GiB): offsets must be 64-bit everywhere.
+
+    Inputs are drawn on the device (seeded) to keep the host out of the way; the first, a middle and
+    the last head - the last one lies wholly beyond the 2^31-element mark - are checked against the
+    oracle, forward and backward, and the end of every output is checked to have been written."""
+    B, H, N, D, causal = 41, 400, 1024, 128, True
+    assert B * H * N * D > 2 ** 31
+    scale = 1 / math.sqrt(D)
+    gen = torch.Generator(device="cuda").manual_seed(2031)
+    print("launch >4GiB tensors", flush=True)
+    q, k, v, d_o = (torch.randn(B, H, N, D, generator=gen, device="cuda", dtype=torch.bfloat16) for _ in range(4))
+    o = torch.full_like(q, 77.0)
+    dq, dk, dv = torch.full_like(q, 77.0), torch.full_like(q, 77.0), torch.full_like(q, 77.0)
+    lse = torch.full((B, H, N), 77.0, dtype=torch.float32, device="cuda")
+    ws = attn.alloc_bwd_workspace(B, H, N, D)
+    assert attn.tk_attn_fwd(q, k, v, o, lse, B, H, N, D, causal, scale) == attn.TK_OK
+    assert attn.tk_attn_bwd(q, k, v, o, d_o, lse, dq, dk, dv, B, H, N, D, causal, scale, ws, ws.numel()) == attn.TK_OK
+    torch.cuda.synchronize()
+    for b, h in ((0, 0), (20, 199), (B - 1, H - 1)):
+        qs, ks, vs, dos = (f64(t[b, h].cpu())[None] for t in (q, k, v, d_o))
+        o_ref, lse_ref = orc.attn_fwd(qs, ks, vs, causal, scale)
+        check_forward(o[b, h][None], lse[b, h][None], o_ref, lse_ref, (b, h))
+        for name, g, r in zip(("dq", "dk", "dv"), (dq, dk, dv), orc.attn_bwd(qs, ks, vs, dos, causal, scale)):
+            assert relf(f64(g[b, h].cpu())[None], r) <= GRAD_RELF, (name, b, h)
+    # no head was skipped: the sentinel survives nowhere (sampled: the last rows of a spread of heads)
+    for t in (o, dq, dk, dv):
+        flat = t.view(B * H, N, D)[:: 997, -1]
+        assert bool((flat != 77.0).any(dim=-1).all())
