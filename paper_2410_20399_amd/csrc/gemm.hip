@@ -170,9 +170,9 @@ void gemm_kernel(const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* _
         read_frags(1, s, 3);
         multiply(0);
         interleave();
-        // every wave holds its last fragments of this stage in registers: the stage can be refilled.
-        // The next stage (issued one step ago) must have landed before its first fragments are read.
-        wait_vmcnt<0>();
+        // Once every wave's last fragment reads of this stage have completed the stage can be refilled;
+        // the next stage (issued one step ago) must have landed before its first fragments are read.
+        __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) and lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         if (s + 2 < n_steps) issue_stage(s + 2);
