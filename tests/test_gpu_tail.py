@@ -90,3 +90,51 @@ def test_tail_forward_backward(attn, B, Hq, Hkv, N, D, causal):
         for b in range(gpu.shape[0]):
             for h in range(gpu.shape[1]):
                 assert relf(gpu[b, h], ref[b, h]) <= GRAD_RELF, (name, b, h)
+
+
+def test_long_ragged_sequence_sampled_through_the_causal_structure(attn):
+    """N = 100003 (781 full tiles and a 35-row tail), causal.  The whole-head oracle is out of reach
+    at this length, but the causal mask makes parts of the result small problems of their own:
+      * the last 200 queries see every key, and the last 200 keys are seen by those queries only:
+        O, LSE, dQ of those queries and dK, dV of those keys = a 200-query x N-key problem;
+      * the first 300 queries see the first 300 keys only: their O, LSE, dQ = the N = 300 problem.
+    """
+    B, H, N, D = 1, 2, 100003, 128
+    T, P = 200, 300
+    scale = 1 / math.sqrt(D)
+    g = torch.Generator().manual_seed(100003)
+    q, k, v, d_o = (torch.randn(B, H, N, D, generator=g).to(torch.bfloat16) for _ in range(4))
+    print(f"launch long ragged sequence N{N}", flush=True)
+    qd, kd, vd, dod = (t.cuda() for t in (q, k, v, d_o))
+    obuf, o = guarded((B, H, N, D), torch.bfloat16, 77.0)
+    lbuf, lse = guarded((B, H, N), torch.float32, 77.0)
+    dqbuf, dq = guarded((B, H, N, D), torch.bfloat16, 77.0)
+    dkbuf, dk = guarded((B, H, N, D), torch.bfloat16, 77.0)
+    dvbuf, dv = guarded((B, H, N, D), torch.bfloat16, 77.0)
+    ws = attn.alloc_bwd_workspace(B, H, N, D)
+    assert attn.tk_attn_fwd(qd, kd, vd, o, lse, B, H, N, D, True, scale) == attn.TK_OK
+    assert attn.tk_attn_bwd(qd, kd, vd, o, dod, lse, dq, dk, dv, B, H, N, D, True, scale, ws, ws.numel()) == attn.TK_OK
+    torch.cuda.synchronize()
+    for buf in (obuf, lbuf, dqbuf, dkbuf, dvbuf):
+        assert bool((buf[-GUARD:] == 77.0).all()), "wrote past the end of an output"
+
+    # the last T queries against all keys
+    o_ref, lse_ref = orc.rect_fwd(f64(q[:, :, -T:]), f64(k), f64(v), True, scale)
+    eo = np.abs(f64(o[:, :, -T:].cpu()) - o_ref)
+    assert eo.max() <= O_MAX and eo.mean() <= O_MEAN, (eo.max(), eo.mean())
+    assert np.abs(f64(lse[:, :, -T:].cpu()) - lse_ref).max() <= LSE_MAX
+    rq, rk, rv = orc.rect_bwd(f64(q[:, :, -T:]), f64(k), f64(v), f64(d_o[:, :, -T:]), True, scale)
+    assert relf(f64(dq[:, :, -T:].cpu()), rq) <= GRAD_RELF
+    assert relf(f64(dk[:, :, -T:].cpu()), rk[:, :, -T:]) <= GRAD_RELF
+    assert relf(f64(dv[:, :, -T:].cpu()), rv[:, :, -T:]) <= GRAD_RELF
+
+    # the first P queries: the N = P problem
+    o_ref, lse_ref = orc.attn_fwd(f64(q[:, :, :P]), f64(k[:, :, :P]), f64(v[:, :, :P]), True, scale)
+    eo = np.abs(f64(o[:, :, :P].cpu()) - o_ref)
+    assert eo.max() <= O_MAX and eo.mean() <= O_MEAN
+    assert np.abs(f64(lse[:, :, :P].cpu()) - lse_ref).max() <= LSE_MAX
+    rq, _, _ = orc.attn_bwd(f64(q[:, :, :P]), f64(k[:, :, :P]), f64(v[:, :, :P]), f64(d_o[:, :, :P]), True, scale)
+    assert relf(f64(dq[:, :, :P].cpu()), rq) <= GRAD_RELF
+    # everything in between was written
+    for t in (o, dq, dk, dv):
+        assert bool((t[:, :, ::1009, :] != 77.0).any(dim=-1).all())
