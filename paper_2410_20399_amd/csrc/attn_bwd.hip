@@ -95,9 +95,11 @@ template <int D> __device__ __forceinline__ int swz(int row) {
     return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
 }
 
-// One wave per SIMD (the dK^T, dV^T accumulators and the K, V fragments take 192 registers at
-// D = 128), so nothing hides LDS latency but the schedule itself.  Every MFMA operand is therefore
-// read one phase ahead of its use:
+// At D = 128: one wave per SIMD (the dK^T, dV^T accumulators and the K, V fragments take 192
+// registers), so nothing hides LDS latency but the schedule itself.  At D = 64 the registers allow
+// two workgroups per compute unit, i.e. two waves per SIMD that fill each other's gaps (the
+// vector work per MFMA is twice that of D = 128 there).  Every MFMA operand is read one phase
+// ahead of its use:
 //     phase 1  S, dP MFMAs from row fragments already in registers; meanwhile the transposed
 //              fragments (dO^T, Q^T) and the statistics of THIS block are read from LDS
 //     phase 2  P, dS on the vector ALU
@@ -105,8 +107,8 @@ template <int D> __device__ __forceinline__ int swz(int row) {
 //              NEXT block are read from LDS
 // and the query blocks themselves arrive by direct global->LDS loads issued three blocks ahead.
 //
-// Nothing hides a workgroup's start-up and wind-down either, so the launch is persistent: one
-// workgroup per compute unit walks the key tiles v = blockIdx.x, blockIdx.x + gridDim.x, ... and
+// Nothing hides a workgroup's start-up and wind-down either, so the launch is persistent: the
+// resident workgroups (one per compute unit, two at D = 64) walk the key tiles v = blockIdx.x, blockIdx.x + gridDim.x, ... and
 // the query-block stream never stops: the loads issued during the last blocks of one key tile
 // already fetch the first blocks of the next, and the next tile's K, V fragments are requested
 // before the current tile's results are stored.
@@ -114,7 +116,7 @@ template <int D> __device__ __forceinline__ int swz(int row) {
 // 128); the aligned square case compiles without any of the tail code.  Causal: query i sees keys
 // j <= i + (Nk - Nq), Nq <= Nk.
 template <int D, bool CAUSAL, bool TAIL>
-__global__ __launch_bounds__(256, 1)
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1)
 void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                           const bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
                           bf16* __restrict__ dK, bf16* __restrict__ dV,
@@ -262,6 +264,10 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     const int trq_lane = trq_row * S::kRowBytes + (((2 * ghalf + ((j16 & 3) >> 1)) ^ swz<D>(trq_row)) << 4) + ((j16 & 1) << 3);
 
     constexpr int kSteps = D / 16;          // MFMA steps of S / dP; also 2 * (D/32) steps of dV^T / dK^T
+    // D = 128: one wave per SIMD, the dV^T / dK^T products of a block run one block late (next to the
+    // following block's vector work).  D = 64: the registers allow two waves per SIMD, which overlap
+    // each other's matrix and vector phases, and the products run in their own block.
+    constexpr bool kDeferred = (D == 128);
     bf16x8 kf[D / 16], vf[D / 16];          // K, V fragments of this wave's 32 keys (B operands of S = Q K^T and dP = dO V^T)
     auto load_kv = [&](int bh, int kt) {
         const int key = kt * S::kTileKV + wave * 32 + l32;
@@ -440,14 +446,24 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         if (CAUSAL) {
 #pragma unroll 1
             for (; blk < n_masked; blk += 2) {
-                step(std::true_type{}, blk, set_a, set_b);
-                step(std::true_type{}, blk + 1, set_b, set_a);
+                if (kDeferred) {
+                    step(std::true_type{}, blk, set_a, set_b);
+                    step(std::true_type{}, blk + 1, set_b, set_a);
+                } else {
+                    step(std::true_type{}, blk, set_a, set_a);
+                    step(std::true_type{}, blk + 1, set_a, set_a);
+                }
             }
         }
 #pragma unroll 1
         for (; blk < n_blocks; blk += 2) {
-            step(std::false_type{}, blk, set_a, set_b);
-            step(std::false_type{}, blk + 1, set_b, set_a);
+            if (kDeferred) {
+                step(std::false_type{}, blk, set_a, set_b);
+                step(std::false_type{}, blk + 1, set_b, set_a);
+            } else {
+                step(std::false_type{}, blk, set_a, set_a);
+                step(std::false_type{}, blk + 1, set_a, set_a);
+            }
         }
         c_count += n_blocks;
     }
@@ -461,8 +477,10 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         load_kv(nbh, nkt);
     }
     // the last block's dV^T / dK^T products
+    if (kDeferred) {
 #pragma unroll
-    for (int idx = 0; idx < kSteps; idx++) late_products(set_b, idx);
+        for (int idx = 0; idx < kSteps; idx++) late_products(set_b, idx);
+    }
 
     // ---- epilogue.  In accumulator layout a lane holds 4 consecutive columns of ONE key row
     // (lane <-> key my_j, register r of block db <-> column 32db + 8*(r/4) + 4h + r%4), so storing
@@ -506,7 +524,8 @@ static hipError_t launch_dkdv_tt(const void* q, const void* k, const void* v, co
     int cus = 0;
     hipError_t e = compute_unit_count(&cus);
     if (e != hipSuccess) return e;
-    const int grid = total_units < cus ? total_units : cus;     // one resident workgroup per compute unit
+    const int resident = cus * (D == 64 ? 2 : 1);               // as many workgroups as fit at once
+    const int grid = total_units < resident ? total_units : resident;
     hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL, TAIL>), dim3(grid), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
                        (bf16*)dk, (bf16*)dv, Nq, Nk, num_kv_tiles, total_units, scale, H, Hkv);
