@@ -147,15 +147,83 @@ def bench_rotary(args, attn, torch, dev, w, x):
     print(json.dumps(out))
 
 
+def bench_decode(args, attn, torch, dev, B=16, Hq=32, Hkv=8, Nk=8192, D=128):
+    """One query per head against a long key/value history: bound by reading K and V once (HBM roofline)."""
+    g = torch.Generator().manual_seed(20399 + 1152)
+    q = torch.randn(B, Hq, 1, D, generator=g).to(torch.bfloat16)
+    k = torch.randn(B, Hkv, Nk, D, generator=g).to(torch.bfloat16)
+    v = torch.randn(B, Hkv, Nk, D, generator=g).to(torch.bfloat16)
+    qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    o = torch.empty_like(qd)
+    lse = torch.empty((B, Hq, 1), dtype=torch.float32, device=dev)
+    need = attn.tk_attn_decode_workspace_bytes(B, Hq, Hkv, Nk, D)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    scale = 1.0 / math.sqrt(D)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        rc = attn.tk_attn_decode(qd, kd, vd, o, lse, B, Hq, Hkv, Nk, D, scale, ws, need, stream)
+        if rc != attn.TK_OK:
+            raise attn.TkAttnError(rc, "tk_attn_decode")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    kernel_ms = e0.elapsed_time(e1) / args.steps              # the split forward and its merge kernel together
+    nbytes = 2 * B * Hkv * Nk * D * 2 + 2 * B * Hq * D * 2 + B * Hq * 4      # K and V once; Q in, O and LSE out
+    gbps = nbytes / (kernel_ms * 1e-3) / 1e9
+    name = f"decode_b{B}_hq{Hq}_hkv{Hkv}_nk{Nk}_d{D}"
+    out = {"metric": f"decode attention GB/s of K and V (bf16, {name})", "value": round(nbytes / (ms_per_step * 1e-3) / 1e9, 1),
+           "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": name, "B": B, "Hq": Hq, "Hkv": Hkv, "Nq": 1, "Nk": Nk, "D": D},
+           "roofline": {"kernel": "attn_fwd_kernel (keys split) + attn_fwd_combine_kernel", "bound": "hbm", "achieved": round(gbps, 1),
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBS, 4),
+                        **measured_traffic(name, "attn_fwd_kernel"), "bytes_per_launch": nbytes}}
+    # the same call through the plain entry point (one workgroup per query head streams the whole history)
+    o2 = torch.empty_like(qd)
+    for _ in range(2):
+        attn.tk_attn_fwd_rect(qd, kd, vd, o2, lse, B, Hq, Hkv, 1, Nk, D, False, scale, stream)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for _ in range(args.steps):
+        attn.tk_attn_fwd_rect(qd, kd, vd, o2, lse, B, Hq, Hkv, 1, Nk, D, False, scale, stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    out["plain_entry_point_ms"] = round(e0.elapsed_time(e1) / args.steps, 4)
+    out["decode_ms"] = round(kernel_ms, 4)
+    if not args.no_cpu_baseline:
+        from oracle import attn_oracle as orc
+        nb = min(B, 4)
+        c0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - c0 < min(args.cpu_seconds, 5.0):
+            orc.rect_fwd(q[:nb].double().numpy(), k[:nb].double().numpy(), v[:nb].double().numpy(), False, scale)
+            reps += 1
+        spent = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": round(reps * nbytes * nb / B / spent / 1e9, 2), "unit": "GB/s (of bf16-sized traffic)",
+                               "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"fp64 oracle on {nb} of {B} batch entries, {reps} passes, {spent:.1f} s"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=6, help="index into workloads.WORKLOADS (default: the target shape)")
-    ap.add_argument("--op", choices=["attention", "rotary", "gemm"], default="attention",
+    ap.add_argument("--op", choices=["attention", "rotary", "gemm", "decode"], default="attention",
                     help="attention (default: the headline fwd+bwd step), the rotary kernel on the same tensor shape, "
-                         "or the bf16 GEMM (8192^3)")
+                         "the bf16 GEMM (8192^3), or the decode-shaped forward (one query per head, B16 Hq32 Hkv8 Nk8192 D128)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle sample")
     ap.add_argument("--no-mfma-probe", action="store_true", help="skip the bare-MFMA ceiling measurement")
@@ -178,6 +246,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.op == "gemm":
         return bench_gemm(args, attn, torch, dev)
+    if args.op == "decode":
+        return bench_decode(args, attn, torch, dev)
     w = workloads.WORKLOADS[args.workload]
     q, k, v, d_o = workloads.make_inputs(w, need_do=True)
     qd, kd, vd, dod = (t.to(dev) for t in (q, k, v, d_o))

@@ -185,6 +185,28 @@ int tk_attn_bwd_rect(const void* q, const void* k, const void* v,
                      void* stream);
 
 /*
+ * Decode-shaped forward: ONE query per head against Nk keys (the Nq = 1 case of tk_attn_fwd_rect,
+ * where the causal mask removes nothing), organised for the memory system rather than the matrix
+ * pipe: the query heads that share a key/value head are processed together, so K and V are read
+ * once per group, and the keys are split over enough workgroups to fill the chip, with a merge of
+ * the partial (O, LSE) pairs behind it.  Results equal tk_attn_fwd_rect's up to fp32 rounding
+ * order of the merge.
+ *
+ *   q, o : bf16 [B, Hq, 1, D]      k, v : bf16 [B, Hkv, Nk, D]      lse : fp32 [B, Hq, 1]
+ *   workspace : device scratch of at least tk_attn_decode_workspace_bytes(B, Hq, Hkv, Nk, D)
+ *               bytes, 16-byte aligned; contents on entry are ignored (partial results live there).
+ * tk_attn_decode_workspace_bytes returns 0 for shapes the call would reject.
+ * Errors as in the calls above, plus TK_ERR_WORKSPACE_TOO_SMALL.
+ */
+size_t tk_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nk, int D);
+
+int tk_attn_decode(const void* q, const void* k, const void* v,
+                   void* o, float* lse,
+                   int B, int Hq, int Hkv, int Nk, int D, float scale,
+                   void* workspace, size_t workspace_bytes,
+                   void* stream);
+
+/*
  * bf16 matrix multiply (the GEMM of the paper's appendix, second workload): C = A B with fp32
  * accumulation and one rounding to bf16.
  *

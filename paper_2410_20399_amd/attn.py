@@ -23,7 +23,8 @@ TK_ERR_LAUNCH = -6
 
 EXPORTS = ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
            "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_attn_fwd_gqa", "tk_attn_bwd_gqa", "tk_attn_bwd_dkdv_gqa",
-           "tk_attn_bwd_dq_gqa", "tk_attn_fwd_rect", "tk_attn_bwd_rect", "tk_rotary", "tk_gemm", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
+           "tk_attn_bwd_dq_gqa", "tk_attn_fwd_rect", "tk_attn_bwd_rect", "tk_attn_decode",
+           "tk_attn_decode_workspace_bytes", "tk_rotary", "tk_gemm", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
 
 _lib = None
 
@@ -69,6 +70,10 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.tk_attn_fwd_rect.restype = i
     lib.tk_attn_bwd_rect.argtypes = [vp, vp, vp, vp, vp, fp, vp, vp, vp, i, i, i, i, i, i, i, f, vp, sz, vp]
     lib.tk_attn_bwd_rect.restype = i
+    lib.tk_attn_decode.argtypes = [vp, vp, vp, vp, fp, i, i, i, i, i, f, vp, sz, vp]
+    lib.tk_attn_decode.restype = i
+    lib.tk_attn_decode_workspace_bytes.argtypes = [i, i, i, i, i]
+    lib.tk_attn_decode_workspace_bytes.restype = sz
     lib.tk_gemm.argtypes = [vp, vp, vp, i, i, i, vp]
     lib.tk_gemm.restype = i
     lib.tk_rotary.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
@@ -167,6 +172,15 @@ def tk_attn_bwd_rect(q, k, v, o, d_o, lse, dq, dk, dv, B, Hq, Hkv, Nq, Nk, D, ca
     return load_library().tk_attn_bwd_rect(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dq),
                                            _ptr(dk), _ptr(dv), B, Hq, Hkv, Nq, Nk, D, int(bool(causal)), float(scale),
                                            _ptr(workspace), int(workspace_bytes), _stream(stream))
+
+
+def tk_attn_decode_workspace_bytes(B, Hq, Hkv, Nk, D) -> int:
+    return int(load_library().tk_attn_decode_workspace_bytes(B, Hq, Hkv, Nk, D))
+
+
+def tk_attn_decode(q, k, v, o, lse, B, Hq, Hkv, Nk, D, scale, workspace, workspace_bytes, stream=None) -> int:
+    return load_library().tk_attn_decode(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, Hq, Hkv, Nk, D,
+                                         float(scale), _ptr(workspace), int(workspace_bytes), _stream(stream))
 
 
 def tk_attn_bwd_dkdv_gqa(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, N, D, causal, scale, stream=None) -> int:
@@ -320,6 +334,25 @@ def rect_bwd(q, k, v, o, d_o, lse, causal: bool, scale: float, workspace=None, s
     if rc != TK_OK:
         raise TkAttnError(rc, "tk_attn_bwd_rect")
     return dq, dk, dv
+
+
+def decode(q, k, v, scale: float, workspace=None, stream=None):
+    """One query per head: q bf16 [B,Hq,1,D], k, v bf16 [B,Hkv,Nk,D]. Returns (o [B,Hq,1,D], lse [B,Hq,1])."""
+    _check_bf16("q", q)
+    B, Hq, one, D = q.shape
+    if one != 1:
+        raise ValueError("decode takes exactly one query per head")
+    Hkv, Nk = k.shape[1], k.shape[2]
+    _check_bf16("k", k, (B, Hkv, Nk, D))
+    _check_bf16("v", v, (B, Hkv, Nk, D))
+    if workspace is None:
+        workspace = torch.empty(max(tk_attn_decode_workspace_bytes(B, Hq, Hkv, Nk, D), 16), dtype=torch.uint8, device=q.device)
+    o = torch.empty_like(q)
+    lse = torch.empty((B, Hq, 1), dtype=torch.float32, device=q.device)
+    rc = tk_attn_decode(q, k, v, o, lse, B, Hq, Hkv, Nk, D, scale, workspace, workspace.numel() * workspace.element_size(), stream)
+    if rc != TK_OK:
+        raise TkAttnError(rc, "tk_attn_decode")
+    return o, lse
 
 
 def rotary(x, sin_table, cos_table, out=None, stream=None):

@@ -49,7 +49,8 @@ template <int D, bool CAUSAL, bool TAIL>
 __global__ __launch_bounds__(256, 2)
 void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                      bf16* __restrict__ O, float* __restrict__ LSE,
-                     int Nq, int Nk, int num_q_tiles, int total_wg, float scale, int hq, int hkv)
+                     int Nq, int Nk, int num_q_tiles, int total_wg, float scale, int hq, int hkv,
+                     int n_splits, int tiles_per_split, float* __restrict__ O_part, float* __restrict__ LSE_part)
 {
     using S = FwdShape<D>;
     // One array per ring stage: distinct LDS objects let the compiler see that reads of the stage
@@ -65,9 +66,14 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
     const int h = lane >> 5;
 
     // workgroup -> (head, query tile); heavy (late) query tiles first when causal
+    // Split over the keys (general-case variant, no mask; used for decode-shaped calls where heads and
+    // query tiles alone cannot fill the chip): n_splits workgroups share one query tile, each takes
+    // tiles_per_split (even) consecutive key tiles and leaves a normalised fp32 partial O and its LSE.
     const int logical = xcd_remap(blockIdx.x, total_wg);
-    const int bh = logical / num_q_tiles;
-    int qt = logical % num_q_tiles;
+    const int split = (TAIL && !CAUSAL) ? logical % n_splits : 0;
+    const int tile_id = (TAIL && !CAUSAL) ? logical / n_splits : logical;
+    const int bh = tile_id / num_q_tiles;
+    int qt = tile_id % num_q_tiles;
     if (CAUSAL) qt = num_q_tiles - 1 - qt;
 
     // grouped-query attention: query head h of a batch entry reads key/value head h / (hq / hkv)
@@ -244,10 +250,15 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
         n_tiles = 2 * ((n_keys + 2 * S::kTileKV - 1) / (2 * S::kTileKV));
     }
 
-    issue_tile(0, 0);
+    int t_begin = 0;
+    if (TAIL && !CAUSAL && n_splits > 1) {
+        t_begin = split * tiles_per_split;
+        if (t_begin + tiles_per_split < n_tiles) n_tiles = t_begin + tiles_per_split;
+    }
+    issue_tile(0, t_begin);
     wait_vmcnt<0>();
     __syncthreads();
-    for (int t = 0; t < n_tiles; t += 2) {
+    for (int t = t_begin; t < n_tiles; t += 2) {
         issue_tile(1, t + 1);
         compute_tile(0, t);
         wait_vmcnt<0>();
@@ -261,7 +272,20 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
     // ---- epilogue
     const float l_tot = half_sum(l_run);
     const float inv = 1.0f / l_tot;
-    if (!TAIL || my_q < Nq) {
+    if (TAIL && !CAUSAL && n_splits > 1) {
+        if (my_q < Nq) {
+            const size_t prow = ((size_t)split * (total_wg / n_splits / num_q_tiles) + bh) * Nq + my_q;   // [split][head][query]
+            float* Op = O_part + prow * D;
+#pragma unroll
+            for (int db = 0; db < D / 32; db++)
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    f32x4 v4 = {o_acc[db][4 * g + 0] * inv, o_acc[db][4 * g + 1] * inv, o_acc[db][4 * g + 2] * inv, o_acc[db][4 * g + 3] * inv};
+                    *(f32x4*)(Op + 32 * db + 8 * g + 4 * h) = v4;
+                }
+            if (h == 0) LSE_part[prow] = m_run * scale + __builtin_logf(l_tot);
+        }
+    } else if (!TAIL || my_q < Nq) {
         bf16* Oh = O + head + (size_t)my_q * D;
 #pragma unroll
         for (int db = 0; db < D / 32; db++)
@@ -277,15 +301,16 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
 
 template <int D, bool CAUSAL, bool TAIL>
 static hipError_t launch_fwd_tt(const void* q, const void* k, const void* v, void* o, float* lse,
-                                int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
+                                int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream,
+                                int n_splits = 1, int tiles_per_split = 0, float* o_part = nullptr, float* lse_part = nullptr)
 {
     using S = FwdShape<D>;
     auto kern = attn_fwd_kernel<D, CAUSAL, TAIL>;
     const int num_q_tiles = (Nq + S::kTileQ - 1) / S::kTileQ;
-    const int total = B * H * num_q_tiles;
+    const int total = B * H * num_q_tiles * n_splits;
     hipLaunchKernelGGL(kern, dim3(total), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (bf16*)o, lse,
-                       Nq, Nk, num_q_tiles, total, scale, H, Hkv);
+                       Nq, Nk, num_q_tiles, total, scale, H, Hkv, n_splits, tiles_per_split, o_part, lse_part);
     return hipGetLastError();
 }
 
@@ -305,6 +330,59 @@ hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, void* o,
                                 : launch_fwd_t<128, false>(q, k, v, o, lse, B, H, Hkv, Nq, Nk, scale, stream);
     return causal ? launch_fwd_t<64, true>(q, k, v, o, lse, B, H, Hkv, Nq, Nk, scale, stream)
                   : launch_fwd_t<64, false>(q, k, v, o, lse, B, H, Hkv, Nq, Nk, scale, stream);
+}
+
+// ------------------------------------------------------------------------------------------
+// merge of the partial results of a split over the keys
+// ------------------------------------------------------------------------------------------
+// O = sum_s w_s O_s / sum_s w_s with w_s = exp(LSE_s - max_s LSE_s), LSE = max + ln sum_s w_s: the
+// partials are softmax results over disjoint key ranges, each normalised by its own sum.
+template <int D>
+__global__ __launch_bounds__(256)
+void attn_fwd_combine_kernel(const float* __restrict__ O_part, const float* __restrict__ LSE_part,
+                             bf16* __restrict__ O, float* __restrict__ LSE, size_t rows, int n_splits)
+{
+    constexpr int kLanesPerRow = D / 4;                 // one float4 per lane
+    const size_t row = (size_t)blockIdx.x * (256 / kLanesPerRow) + threadIdx.x / kLanesPerRow;
+    if (row >= rows) return;
+    const int col = (threadIdx.x % kLanesPerRow) * 4;
+    float m = -INFINITY;
+    for (int s = 0; s < n_splits; s++) m = __builtin_fmaxf(m, LSE_part[(size_t)s * rows + row]);
+    float wsum = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < n_splits; s++) {
+        const float w = __builtin_expf(LSE_part[(size_t)s * rows + row] - m);
+        const f32x4 v = *(const f32x4*)(O_part + ((size_t)s * rows + row) * D + col);
+        wsum += w;
+        acc += v * w;
+    }
+    const float inv = 1.0f / wsum;
+    bf16x2 lo = cvt2(acc[0] * inv, acc[1] * inv), hi = cvt2(acc[2] * inv, acc[3] * inv);
+    *(bf16x4*)(O + row * D + col) = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+    if (col == 0) LSE[row] = m + __builtin_logf(wsum);
+}
+
+// Non-causal forward with the keys split n_splits ways (n_splits >= 2, every split holds at least one
+// key: (n_splits - 1) * tiles_per_split * 64 < Nk, tiles_per_split even).  o_part: fp32
+// [n_splits][B*H][Nq][D], lse_part: fp32 [n_splits][B*H][Nq].
+hipError_t launch_attn_fwd_splitk(const void* q, const void* k, const void* v, void* o, float* lse,
+                                  float* o_part, float* lse_part,
+                                  int B, int H, int Hkv, int Nq, int Nk, int D, float scale,
+                                  int n_splits, int tiles_per_split, hipStream_t stream)
+{
+    hipError_t e = D == 128
+        ? launch_fwd_tt<128, false, true>(q, k, v, o, lse, B, H, Hkv, Nq, Nk, scale, stream, n_splits, tiles_per_split, o_part, lse_part)
+        : launch_fwd_tt<64, false, true>(q, k, v, o, lse, B, H, Hkv, Nq, Nk, scale, stream, n_splits, tiles_per_split, o_part, lse_part);
+    if (e != hipSuccess) return e;
+    const size_t rows = (size_t)B * H * Nq;
+    if (D == 128) {
+        const unsigned grid = (unsigned)((rows + 7) / 8);
+        hipLaunchKernelGGL((attn_fwd_combine_kernel<128>), dim3(grid), dim3(256), 0, stream, o_part, lse_part, (bf16*)o, lse, rows, n_splits);
+    } else {
+        const unsigned grid = (unsigned)((rows + 15) / 16);
+        hipLaunchKernelGGL((attn_fwd_combine_kernel<64>), dim3(grid), dim3(256), 0, stream, o_part, lse_part, (bf16*)o, lse, rows, n_splits);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace tk

@@ -41,6 +41,39 @@ int check_lengths(int B, int H, int Nq, int Nk, int D, int causal)
     return TK_OK;
 }
 
+// Decode-shaped calls: one query per head against Nk keys.
+constexpr int kDecodeMaxSplits = 64;       // upper bound on the split over the keys (sizes the workspace)
+constexpr int kDecodeMinTiles = 4;         // a split holds at least this many 64-key tiles
+constexpr int kDecodeMaxPackedRows = 128;  // query heads of one group packed into the rows of one tile
+
+struct DecodePlan {
+    int b, h, hkv, nq;       // the call as the forward kernel sees it
+    int n_splits, tiles_per_split;
+};
+
+// The query heads that share a key/value head are contiguous [G, D] rows when every head has one query:
+// they are handed to the kernel as ONE head of G queries (so K and V are streamed once per group, not once
+// per query head).  The keys are split so that about two workgroups per compute unit are in flight.
+DecodePlan plan_decode(int B, int Hq, int Hkv, int Nk, int compute_units)
+{
+    DecodePlan p;
+    const int G = Hq / Hkv;
+    if (G <= kDecodeMaxPackedRows) { p.b = B * Hkv; p.h = 1; p.hkv = 1; p.nq = G; }
+    else                           { p.b = B; p.h = Hq; p.hkv = Hkv; p.nq = 1; }
+    const long long base = (long long)p.b * p.h;
+    const int tiles = (Nk + 63) / 64;
+    long long want = (2LL * compute_units + base - 1) / base;
+    const int by_tiles = tiles / kDecodeMinTiles;
+    if (want > by_tiles) want = by_tiles;
+    if (want > kDecodeMaxSplits) want = kDecodeMaxSplits;
+    if (want < 1) want = 1;
+    int per = (int)((tiles + want - 1) / want);
+    per += per & 1;                                   // the kernel walks the tiles in pairs
+    p.tiles_per_split = per;
+    p.n_splits = (tiles + per - 1) / per;             // no split is empty
+    return p;
+}
+
 int check_heads(int H, int Hkv)
 {
     return (Hkv >= 1 && Hkv <= H && H % Hkv == 0) ? TK_OK : TK_ERR_BAD_DIM;
@@ -72,6 +105,44 @@ int tk_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse
                 int B, int H, int N, int D, int causal, float scale, void* stream)
 {
     return tk_attn_fwd_gqa(q, k, v, o, lse, B, H, H, N, D, causal, scale, stream);
+}
+
+size_t tk_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nk, int D)
+{
+    if (check_shape(B, Hq, Nk, D) != TK_OK || check_heads(Hq, Hkv) != TK_OK) return 0;
+    // partial O (fp32 [splits][B*Hq][D]) and partial LSE (fp32 [splits][B*Hq]), each padded to 256 bytes
+    const size_t rows = (size_t)B * Hq;
+    const size_t o_bytes = ((size_t)kDecodeMaxSplits * rows * D * sizeof(float) + 255) & ~(size_t)255;
+    const size_t l_bytes = ((size_t)kDecodeMaxSplits * rows * sizeof(float) + 255) & ~(size_t)255;
+    return o_bytes + l_bytes;
+}
+
+int tk_attn_decode(const void* q, const void* k, const void* v, void* o, float* lse,
+                   int B, int Hq, int Hkv, int Nk, int D, float scale,
+                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k || !v || !o || !lse || !workspace) return TK_ERR_NULL_PTR;
+    if (int rc = check_shape(B, Hq, Nk, D)) return rc;
+    if (int rc = check_heads(Hq, Hkv)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(workspace))
+        return TK_ERR_MISALIGNED;
+    if (int rc = check_scale(scale)) return rc;
+    if (workspace_bytes < tk_attn_decode_workspace_bytes(B, Hq, Hkv, Nk, D)) return TK_ERR_WORKSPACE_TOO_SMALL;
+
+    int cus = 0;
+    if (tk::compute_unit_count(&cus) != hipSuccess || cus < 1) return TK_ERR_LAUNCH;
+    const DecodePlan p = plan_decode(B, Hq, Hkv, Nk, cus);
+    hipError_t e;
+    if (p.n_splits == 1) {
+        e = tk::launch_attn_fwd(q, k, v, o, lse, p.b, p.h, p.hkv, p.nq, Nk, D, 0, scale, (hipStream_t)stream);
+    } else {
+        const size_t rows = (size_t)B * Hq;
+        float* o_part = (float*)workspace;
+        float* lse_part = (float*)((char*)workspace + (((size_t)kDecodeMaxSplits * rows * D * sizeof(float) + 255) & ~(size_t)255));
+        e = tk::launch_attn_fwd_splitk(q, k, v, o, lse, o_part, lse_part, p.b, p.h, p.hkv, p.nq, Nk, D, scale,
+                                       p.n_splits, p.tiles_per_split, (hipStream_t)stream);
+    }
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
 }
 
 size_t tk_attn_bwd_workspace_bytes(int B, int H, int N, int D)

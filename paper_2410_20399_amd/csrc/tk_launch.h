@@ -19,6 +19,14 @@ inline hipError_t compute_unit_count(int* cus) {
 hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                            int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream);
 
+// The same forward, non-causal, with the keys split n_splits (>= 2) ways and a merge kernel behind it
+// (decode-shaped calls).  o_part: fp32 [n_splits][B*H][Nq][D]; lse_part: fp32 [n_splits][B*H][Nq];
+// tiles_per_split: even number of 64-key tiles per split, (n_splits - 1) * tiles_per_split * 64 < Nk.
+hipError_t launch_attn_fwd_splitk(const void* q, const void* k, const void* v, void* o, float* lse,
+                                  float* o_part, float* lse_part,
+                                  int B, int H, int Hkv, int Nq, int Nk, int D, float scale,
+                                  int n_splits, int tiles_per_split, hipStream_t stream);
+
 // Delta_i = sum_d dO_id O_id
 hipError_t launch_attn_bwd_delta(const void* o, const void* d_o, float* delta,
                                  int B, int H, int N, int D, hipStream_t stream);

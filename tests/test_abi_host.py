@@ -173,6 +173,31 @@ def test_rect_entries_reject_bad_arguments(lib):
     assert bwd_rect(ws_bytes=need - 1) == a.TK_ERR_WORKSPACE_TOO_SMALL
 
 
+def test_decode_entry_rejects_bad_arguments(lib):
+    from paper_2410_20399_amd import attn as a
+    f = ctypes.c_float
+    sz = ctypes.c_size_t
+
+    def decode(*, q=P, lse=P, ws=P, Hq=8, Hkv=2, Nk=1000, D=128, scale=0.1, ws_bytes=1 << 40):
+        return lib.tk_attn_decode(q, P, P, P, lse, 2, Hq, Hkv, Nk, D, f(scale), ws, sz(ws_bytes), None)
+
+    assert decode(q=None) == a.TK_ERR_NULL_PTR
+    assert decode(ws=None) == a.TK_ERR_NULL_PTR
+    assert decode(lse=ODD) == a.TK_ERR_MISALIGNED
+    assert decode(ws=ODD) == a.TK_ERR_MISALIGNED
+    assert decode(Nk=0) == a.TK_ERR_BAD_DIM
+    assert decode(D=32) == a.TK_ERR_BAD_DIM
+    assert decode(Hq=8, Hkv=3) == a.TK_ERR_BAD_DIM
+    assert decode(scale=float("nan")) == a.TK_ERR_BAD_SCALE
+    need = lib.tk_attn_decode_workspace_bytes(2, 8, 2, 1000, 128)
+    # 64 splits at most: fp32 partial O [64][B*Hq][D] and partial LSE [64][B*Hq]
+    assert need == 64 * 16 * 128 * 4 + 64 * 16 * 4
+    assert need % 256 == 0
+    assert decode(ws_bytes=need - 1) == a.TK_ERR_WORKSPACE_TOO_SMALL
+    assert lib.tk_attn_decode_workspace_bytes(2, 8, 3, 1000, 128) == 0
+    assert lib.tk_attn_decode_workspace_bytes(2, 8, 2, 0, 128) == 0
+
+
 def test_gemm_rejects_bad_arguments(lib):
     from paper_2410_20399_amd import attn as a
     for i in range(3):
