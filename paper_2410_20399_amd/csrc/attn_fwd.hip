@@ -159,6 +159,7 @@ void attn_fwd_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, con
     auto compute_tile = [&](int stage, int tile) {
         const int j0 = tile * S::kTileKV;
         if (CAUSAL && j0 > q0 + 31 + off) return;    // every key of the tile is masked for this wave
+        if (TAIL && q0 >= Nq) return;                // a wave of padding rows only (few queries, e.g. decode)
         const char* ks = stage ? smem1 : smem0;
         const char* vs = ks + S::kTileBytes;
 

@@ -42,7 +42,9 @@ int check_lengths(int B, int H, int Nq, int Nk, int D, int causal)
 }
 
 // Decode-shaped calls: one query per head against Nk keys.
-constexpr int kDecodeMaxSplits = 64;       // upper bound on the split over the keys (sizes the workspace)
+constexpr int kDecodeMaxSplits = 256;      // upper bound on the split over the keys
+constexpr int kDecodeMaxWorkgroups = 1024; // no more splits than it takes to reach this many workgroups (sizes the workspace)
+constexpr int kDecodeWgPerCu = 2;          // workgroups per compute unit the split aims at (measured best on long histories)
 constexpr int kDecodeMinTiles = 4;         // a split holds at least this many 64-key tiles
 constexpr int kDecodeMaxPackedRows = 128;  // query heads of one group packed into the rows of one tile
 
@@ -50,6 +52,16 @@ struct DecodePlan {
     int b, h, hkv, nq;       // the call as the forward kernel sees it
     int n_splits, tiles_per_split;
 };
+
+// most splits a call of this shape can get, whatever the device (the workspace is sized by it)
+int decode_max_splits(int B, int Hq, int Hkv)
+{
+    const int G = Hq / Hkv;
+    const long long base = G <= kDecodeMaxPackedRows ? (long long)B * Hkv : (long long)B * Hq;
+    long long s = (kDecodeMaxWorkgroups + base - 1) / base;
+    if (s > kDecodeMaxSplits) s = kDecodeMaxSplits;
+    return s < 1 ? 1 : (int)s;
+}
 
 // The query heads that share a key/value head are contiguous [G, D] rows when every head has one query:
 // they are handed to the kernel as ONE head of G queries (so K and V are streamed once per group, not once
@@ -62,10 +74,11 @@ DecodePlan plan_decode(int B, int Hq, int Hkv, int Nk, int compute_units)
     else                           { p.b = B; p.h = Hq; p.hkv = Hkv; p.nq = 1; }
     const long long base = (long long)p.b * p.h;
     const int tiles = (Nk + 63) / 64;
-    long long want = (2LL * compute_units + base - 1) / base;
+    long long want = ((long long)kDecodeWgPerCu * compute_units + base - 1) / base;
     const int by_tiles = tiles / kDecodeMinTiles;
+    const int by_shape = decode_max_splits(B, Hq, Hkv);
     if (want > by_tiles) want = by_tiles;
-    if (want > kDecodeMaxSplits) want = kDecodeMaxSplits;
+    if (want > by_shape) want = by_shape;
     if (want < 1) want = 1;
     int per = (int)((tiles + want - 1) / want);
     per += per & 1;                                   // the kernel walks the tiles in pairs
@@ -111,9 +124,9 @@ size_t tk_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nk, int D)
 {
     if (check_shape(B, Hq, Nk, D) != TK_OK || check_heads(Hq, Hkv) != TK_OK) return 0;
     // partial O (fp32 [splits][B*Hq][D]) and partial LSE (fp32 [splits][B*Hq]), each padded to 256 bytes
-    const size_t rows = (size_t)B * Hq;
-    const size_t o_bytes = ((size_t)kDecodeMaxSplits * rows * D * sizeof(float) + 255) & ~(size_t)255;
-    const size_t l_bytes = ((size_t)kDecodeMaxSplits * rows * sizeof(float) + 255) & ~(size_t)255;
+    const size_t rows = (size_t)B * Hq, splits = (size_t)decode_max_splits(B, Hq, Hkv);
+    const size_t o_bytes = (splits * rows * D * sizeof(float) + 255) & ~(size_t)255;
+    const size_t l_bytes = (splits * rows * sizeof(float) + 255) & ~(size_t)255;
     return o_bytes + l_bytes;
 }
 
@@ -138,7 +151,7 @@ int tk_attn_decode(const void* q, const void* k, const void* v, void* o, float* 
     } else {
         const size_t rows = (size_t)B * Hq;
         float* o_part = (float*)workspace;
-        float* lse_part = (float*)((char*)workspace + (((size_t)kDecodeMaxSplits * rows * D * sizeof(float) + 255) & ~(size_t)255));
+        float* lse_part = (float*)((char*)workspace + (((size_t)decode_max_splits(B, Hq, Hkv) * rows * D * sizeof(float) + 255) & ~(size_t)255));
         e = tk::launch_attn_fwd_splitk(q, k, v, o, lse, o_part, lse_part, p.b, p.h, p.hkv, p.nq, Nk, D, scale,
                                        p.n_splits, p.tiles_per_split, (hipStream_t)stream);
     }

@@ -190,8 +190,10 @@ def test_decode_entry_rejects_bad_arguments(lib):
     assert decode(Hq=8, Hkv=3) == a.TK_ERR_BAD_DIM
     assert decode(scale=float("nan")) == a.TK_ERR_BAD_SCALE
     need = lib.tk_attn_decode_workspace_bytes(2, 8, 2, 1000, 128)
-    # 64 splits at most: fp32 partial O [64][B*Hq][D] and partial LSE [64][B*Hq]
-    assert need == 64 * 16 * 128 * 4 + 64 * 16 * 4
+    # B*Hkv = 4 packed heads -> at most 256 splits: fp32 partial O [256][B*Hq][D] and partial LSE [256][B*Hq]
+    assert need == 256 * 16 * 128 * 4 + 256 * 16 * 4
+    # 512 packed heads -> at most 2 splits
+    assert lib.tk_attn_decode_workspace_bytes(64, 32, 8, 1000, 64) == 2 * 2048 * 64 * 4 + 2 * 2048 * 4
     assert need % 256 == 0
     assert decode(ws_bytes=need - 1) == a.TK_ERR_WORKSPACE_TOO_SMALL
     assert lib.tk_attn_decode_workspace_bytes(2, 8, 3, 1000, 128) == 0
