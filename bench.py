@@ -31,6 +31,7 @@ MEASURED_TRAFFIC = {
     "fwdbwd_causal_b16_h16_n4096_d128": {"kernel": "attn_bwd_dkdv_kernel", "bytes": 1.245e9 + 0.537e9,
                                          "source": "profiles/bench_fwdbwd_causal_b16_h16_n4096_d128.txt"},
     "gemm_8192x8192x8192": {"kernel": "gemm_kernel", "bytes": 1.61e9 + 0.148e9, "source": "profiles/gemm_8192x8192x8192.txt"},
+    "decode_b16_hq32_hkv8_nk8192_d128": {"kernel": "attn_fwd_kernel", "bytes": 537.2e6 + 0.54e6, "source": "profiles/decode_b16_hq32_hkv8_nk8192_d128.txt"},
     "rotary_fwdbwd_causal_b16_h16_n4096_d128": {"kernel": "rotary_kernel", "bytes": 0.270e9 + 0.268e9, "source": "profiles/rotary_b16_h16_n4096_d128.txt"},
 }
 
