@@ -207,6 +207,17 @@ int tk_attn_decode(const void* q, const void* k, const void* v,
                    void* stream);
 
 /*
+ * How tk_attn_decode would lay a call out on a device with `compute_units` compute units (host
+ * arithmetic only; for callers that want to know, and for tests):
+ *   plan[0] heads as the kernel sees them (B*Hkv when a group's query heads are packed, else B*Hq)
+ *   plan[1] query rows per such head (Hq/Hkv when packed, else 1)
+ *   plan[2] splits over the keys        plan[3] 64-key tiles per split (even)
+ *   plan[4] most splits any device could give this shape (what the workspace is sized for)
+ * plan: host pointer to 5 ints.  Errors: TK_ERR_NULL_PTR, TK_ERR_BAD_DIM.
+ */
+int tk_attn_decode_plan(int B, int Hq, int Hkv, int Nk, int D, int compute_units, int* plan);
+
+/*
  * bf16 matrix multiply (the GEMM of the paper's appendix, second workload): C = A B with fp32
  * accumulation and one rounding to bf16.
  *

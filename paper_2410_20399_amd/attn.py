@@ -24,7 +24,7 @@ TK_ERR_LAUNCH = -6
 EXPORTS = ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
            "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_attn_fwd_gqa", "tk_attn_bwd_gqa", "tk_attn_bwd_dkdv_gqa",
            "tk_attn_bwd_dq_gqa", "tk_attn_fwd_rect", "tk_attn_bwd_rect", "tk_attn_decode",
-           "tk_attn_decode_workspace_bytes", "tk_rotary", "tk_gemm", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
+           "tk_attn_decode_workspace_bytes", "tk_attn_decode_plan", "tk_rotary", "tk_gemm", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
 
 _lib = None
 
@@ -72,6 +72,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.tk_attn_bwd_rect.restype = i
     lib.tk_attn_decode.argtypes = [vp, vp, vp, vp, fp, i, i, i, i, i, f, vp, sz, vp]
     lib.tk_attn_decode.restype = i
+    lib.tk_attn_decode_plan.argtypes = [i, i, i, i, i, i, ctypes.POINTER(ctypes.c_int)]
+    lib.tk_attn_decode_plan.restype = i
     lib.tk_attn_decode_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.tk_attn_decode_workspace_bytes.restype = sz
     lib.tk_gemm.argtypes = [vp, vp, vp, i, i, i, vp]
@@ -176,6 +178,13 @@ def tk_attn_bwd_rect(q, k, v, o, d_o, lse, dq, dk, dv, B, Hq, Hkv, Nq, Nk, D, ca
 
 def tk_attn_decode_workspace_bytes(B, Hq, Hkv, Nk, D) -> int:
     return int(load_library().tk_attn_decode_workspace_bytes(B, Hq, Hkv, Nk, D))
+
+
+def tk_attn_decode_plan(B, Hq, Hkv, Nk, D, compute_units):
+    """(status, [heads, rows per head, splits, tiles per split, max splits]) - host arithmetic only."""
+    plan = (ctypes.c_int * 5)()
+    rc = load_library().tk_attn_decode_plan(B, Hq, Hkv, Nk, D, compute_units, plan)
+    return rc, list(plan)
 
 
 def tk_attn_decode(q, k, v, o, lse, B, Hq, Hkv, Nk, D, scale, workspace, workspace_bytes, stream=None) -> int:

@@ -120,6 +120,21 @@ int tk_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse
     return tk_attn_fwd_gqa(q, k, v, o, lse, B, H, H, N, D, causal, scale, stream);
 }
 
+int tk_attn_decode_plan(int B, int Hq, int Hkv, int Nk, int D, int compute_units, int* plan)
+{
+    if (!plan) return TK_ERR_NULL_PTR;
+    if (int rc = check_shape(B, Hq, Nk, D)) return rc;
+    if (int rc = check_heads(Hq, Hkv)) return rc;
+    if (compute_units < 1) return TK_ERR_BAD_DIM;
+    const DecodePlan p = plan_decode(B, Hq, Hkv, Nk, compute_units);
+    plan[0] = p.b * p.h;
+    plan[1] = p.nq;
+    plan[2] = p.n_splits;
+    plan[3] = p.tiles_per_split;
+    plan[4] = decode_max_splits(B, Hq, Hkv);
+    return TK_OK;
+}
+
 size_t tk_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nk, int D)
 {
     if (check_shape(B, Hq, Nk, D) != TK_OK || check_heads(Hq, Hkv) != TK_OK) return 0;

@@ -200,6 +200,35 @@ def test_decode_entry_rejects_bad_arguments(lib):
     assert lib.tk_attn_decode_workspace_bytes(2, 8, 2, 0, 128) == 0
 
 
+def test_decode_plan_invariants(lib):
+    """Host arithmetic of the decode layout: no empty split, even tile counts, splits within the bound
+    the workspace is sized for, grouped heads packed while they fit one tile."""
+    from paper_2410_20399_amd import attn as a
+    import itertools
+    for B, (Hq, Hkv), Nk, D, cus in itertools.product(
+            (1, 2, 16, 300), ((1, 1), (8, 8), (32, 8), (128, 1), (129, 1), (256, 2)),
+            (1, 63, 64, 65, 255, 256, 1000, 8192, 100000, 1 << 20), (64, 128), (1, 64, 256, 304)):
+        rc, (heads, rows, splits, per, max_splits) = a.tk_attn_decode_plan(B, Hq, Hkv, Nk, D, cus)
+        if B * Hq * Nk > 0x7fffffff * 16:                 # beyond what any entry point accepts
+            assert rc == a.TK_ERR_BAD_DIM
+            continue
+        assert rc == a.TK_OK
+        G = Hq // Hkv
+        assert (heads, rows) == ((B * Hkv, G) if G <= 128 else (B * Hq, 1))
+        tiles = (Nk + 63) // 64
+        assert 1 <= splits <= max_splits <= 256
+        assert per % 2 == 0 and per >= 2
+        assert splits * per >= tiles                      # the splits cover every tile
+        assert (splits - 1) * per * 64 < Nk               # and the last one still holds a key
+        if splits > 1:
+            assert per >= 4 and heads * (splits - 1) < 2 * cus + heads      # no more splits than fill two workgroups per unit
+        need = lib.tk_attn_decode_workspace_bytes(B, Hq, Hkv, Nk, D)
+        assert need >= splits * B * Hq * (D + 1) * 4
+    assert a.tk_attn_decode_plan(1, 8, 3, 100, 64, 256)[0] == a.TK_ERR_BAD_DIM
+    assert a.tk_attn_decode_plan(1, 8, 2, 100, 64, 0)[0] == a.TK_ERR_BAD_DIM
+    assert lib.tk_attn_decode_plan(1, 8, 2, 100, 64, 256, None) == a.TK_ERR_NULL_PTR
+
+
 def test_gemm_rejects_bad_arguments(lib):
     from paper_2410_20399_amd import attn as a
     for i in range(3):
