@@ -73,10 +73,7 @@ struct DkdvShape {
     static constexpr int kThreads = 256;
     static constexpr int kTileKV = 128;                 // keys per workgroup (32 per wave)
     static constexpr int kTileQ = 32;                   // queries per loop iteration
-#ifndef TK_DKDV_STAGES
-#define TK_DKDV_STAGES 4
-#endif
-    static constexpr int kStages = TK_DKDV_STAGES;      // LDS ring of query blocks (a power of two), filled kStages-1 blocks ahead
+    static constexpr int kStages = 4;                   // LDS ring of query blocks (a power of two), filled kStages-1 blocks ahead
     static constexpr int kAhead = kStages - 1;
     static constexpr int kRowBytes = D * 2;
     static constexpr int kChunksPerRow = D / 8;
