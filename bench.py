@@ -302,12 +302,15 @@ def main():
 
     # ---- per-kernel durations: the same kernels through the stage entry points, HIP events on the launch stream
 
+    # the backward runs two kernels: dQ with Delta folded in, then dK/dV; the stand-alone Delta pass
+    # (tk_attn_bwd_delta, an HBM stream over O and dO) is timed too, as the HBM-bound reference point
+    dq_delta_call = lambda: attn.tk_attn_bwd_dq_delta(qd, kd, vd, o, dod, lse, delta, dq, B, H, Hkv, N, D, w.causal, w.scale, stream)
     stages = [("attn_fwd_kernel", lambda: check(fwd_call(), "fwd"))]
     if w.backward:
         stages += [
-            ("attn_bwd_delta_kernel", lambda: check(attn.tk_attn_bwd_delta(o, dod, delta, B, H, N, D, stream), "delta")),
+            ("attn_bwd_dq_kernel", lambda: check(dq_delta_call(), "dq+delta")),
             ("attn_bwd_dkdv_kernel", lambda: check(dkdv_call(), "dkdv")),
-            ("attn_bwd_dq_kernel", lambda: check(dq_call(), "dq")),
+            ("attn_bwd_delta_kernel", lambda: check(attn.tk_attn_bwd_delta(o, dod, delta, B, H, N, D, stream), "delta")),
         ]
     kernel_ms = {name: 0.0 for name, _ in stages}
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)] for _ in range(args.steps)]
@@ -336,7 +339,7 @@ def main():
         "kernel_ms": {k_: round(v_, 4) for k_, v_ in kernel_ms.items()},
     }
     if w.backward:
-        bwd_ms = kernel_ms["attn_bwd_delta_kernel"] + kernel_ms["attn_bwd_dkdv_kernel"] + kernel_ms["attn_bwd_dq_kernel"]
+        bwd_ms = kernel_ms["attn_bwd_dq_kernel"] + kernel_ms["attn_bwd_dkdv_kernel"]       # what tk_attn_bwd launches
         bwd_tflops = flops_bwd / (bwd_ms * 1e-3) / 1e12
         # the dK/dV kernel executes four of the backward's five products
         # (S, dP, dV, dK: 8*D flops per kept query-key pair); the dQ kernel three (S, dP, dQ: 6*D)

@@ -147,7 +147,20 @@ int tk_attn_bwd_gqa(const void* q, const void* k, const void* v,
                     void* workspace, size_t workspace_bytes,
                     void* stream);
 
-/* Stages 2 and 3 of tk_attn_bwd_gqa (stage 1 is tk_attn_bwd_delta with H = Hq). */
+/*
+ * The two stages tk_attn_bwd / _gqa / _rect actually run: the dQ kernel with Delta folded in, then the
+ * dK/dV kernel.  A lane of the dQ kernel holds its query's dO row already, so it reads the matching O
+ * row, forms Delta_i = sum_d dO_id O_id, uses it and writes it out; the separate pass over O and dO
+ * (tk_attn_bwd_delta) is then not needed.  Hkv == Hq: plain multi-head.
+ *   o     : in,  bf16 [B, Hq, N, D] (the forward's output)
+ *   delta : out, fp32 [B, Hq, N]    (input of tk_attn_bwd_dkdv / _dkdv_gqa afterwards)
+ *   dq    : out, bf16 [B, Hq, N, D]
+ */
+int tk_attn_bwd_dq_delta(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                         const float* lse, float* delta, void* dq,
+                         int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream);
+
+/* Stages 2 and 3 of the three-stage form (stage 1 is tk_attn_bwd_delta with H = Hq). */
 int tk_attn_bwd_dkdv_gqa(const void* q, const void* k, const void* v, const void* d_o,
                          const float* lse, const float* delta,
                          void* dk, void* dv,

@@ -23,7 +23,7 @@ TK_ERR_LAUNCH = -6
 
 EXPORTS = ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
            "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_attn_fwd_gqa", "tk_attn_bwd_gqa", "tk_attn_bwd_dkdv_gqa",
-           "tk_attn_bwd_dq_gqa", "tk_attn_fwd_rect", "tk_attn_bwd_rect", "tk_attn_decode",
+           "tk_attn_bwd_dq_gqa", "tk_attn_bwd_dq_delta", "tk_attn_fwd_rect", "tk_attn_bwd_rect", "tk_attn_decode",
            "tk_attn_decode_workspace_bytes", "tk_attn_decode_plan", "tk_rotary", "tk_gemm", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
 
 _lib = None
@@ -66,6 +66,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.tk_attn_bwd_dkdv_gqa.restype = i
     lib.tk_attn_bwd_dq_gqa.argtypes = [vp, vp, vp, vp, fp, fp, vp, i, i, i, i, i, i, f, vp]
     lib.tk_attn_bwd_dq_gqa.restype = i
+    lib.tk_attn_bwd_dq_delta.argtypes = [vp, vp, vp, vp, vp, fp, fp, vp, i, i, i, i, i, i, f, vp]
+    lib.tk_attn_bwd_dq_delta.restype = i
     lib.tk_attn_fwd_rect.argtypes = [vp, vp, vp, vp, fp, i, i, i, i, i, i, i, f, vp]
     lib.tk_attn_fwd_rect.restype = i
     lib.tk_attn_bwd_rect.argtypes = [vp, vp, vp, vp, vp, fp, vp, vp, vp, i, i, i, i, i, i, i, f, vp, sz, vp]
@@ -162,6 +164,11 @@ def tk_attn_bwd_gqa(q, k, v, o, d_o, lse, dq, dk, dv, B, Hq, Hkv, N, D, causal, 
     return load_library().tk_attn_bwd_gqa(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dq),
                                           _ptr(dk), _ptr(dv), B, Hq, Hkv, N, D, int(bool(causal)), float(scale),
                                           _ptr(workspace), int(workspace_bytes), _stream(stream))
+
+
+def tk_attn_bwd_dq_delta(q, k, v, o, d_o, lse, delta, dq, B, Hq, Hkv, N, D, causal, scale, stream=None) -> int:
+    return load_library().tk_attn_bwd_dq_delta(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(delta),
+                                               _ptr(dq), B, Hq, Hkv, N, D, int(bool(causal)), float(scale), _stream(stream))
 
 
 def tk_attn_fwd_rect(q, k, v, o, lse, B, Hq, Hkv, Nq, Nk, D, causal, scale, stream=None) -> int:

@@ -566,11 +566,15 @@ struct DqShape {
     static constexpr int kLoadsPerTile = kTileKV * kChunksPerRow / kThreads;   // per thread, per tensor
 };
 
-template <int D, bool CAUSAL, bool TAIL>
+// FUSED: Delta is not an input: the kernel computes Delta_i = sum_d dO_id O_id for its own rows (a
+// lane already holds its query's dO row), writes it to DeltaOut for the dK/dV kernel that follows,
+// and uses it; the separate Delta pass over O and dO is then not needed.
+template <int D, bool CAUSAL, bool TAIL, bool FUSED>
 __global__ __launch_bounds__(256, 2)
 void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                         const bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
-                        bf16* __restrict__ dQ, int Nq, int Nk, int num_q_tiles, int total_wg, float scale, int hq, int hkv)
+                        bf16* __restrict__ dQ, int Nq, int Nk, int num_q_tiles, int total_wg, float scale, int hq, int hkv,
+                        const bf16* __restrict__ O, float* __restrict__ DeltaOut)
 {
     using S = DqShape<D>;
     __shared__ __attribute__((aligned(1024))) char stage0[S::kStageBytes];
@@ -615,7 +619,20 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
         dof[kb] = *(const bf16x8*)(dO + head + (size_t)my_q_ld * D + kb * 16 + h * 8);
     }
     const float lse2 = LSE[(size_t)bh * Nq + my_q_ld] * kLog2e;
-    const float delta = Delta[(size_t)bh * Nq + my_q_ld];
+    float delta;
+    if (FUSED) {
+        float part = 0.f;       // this lane's half of the row (columns 16*kb + 8*h .. +7)
+#pragma unroll
+        for (int kb = 0; kb < D / 16; kb++) {
+            const bf16x8 of = *(const bf16x8*)(O + head + (size_t)my_q_ld * D + kb * 16 + h * 8);
+#pragma unroll
+            for (int e = 0; e < 8; e++) part = __builtin_fmaf((float)of[e], (float)dof[kb][e], part);
+        }
+        delta = half_sum(part);
+        if (h == 0 && (!TAIL || my_q < Nq)) DeltaOut[(size_t)bh * Nq + my_q] = delta;
+    } else {
+        delta = Delta[(size_t)bh * Nq + my_q_ld];
+    }
 
     // ---- direct-to-LDS tile loads (same slot arithmetic as the forward kernel)
     int kv_src[S::kLoadsPerTile];
@@ -753,39 +770,45 @@ void attn_bwd_dq_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, 
     }   // pass (the loop above ends with a barrier, so both stages are free again)
 }
 
-template <int D, bool CAUSAL, bool TAIL>
+template <int D, bool CAUSAL, bool TAIL, bool FUSED>
 static hipError_t launch_dq_tt(const void* q, const void* k, const void* v, const void* d_o,
                                const float* lse, const float* delta, void* dq,
-                               int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
+                               int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream,
+                               const void* o, float* delta_out)
 {
     using S = DqShape<D>;
     const int num_q_tiles = (Nq + S::kTileQ - 1) / S::kTileQ;
     const int total = B * H * (CAUSAL ? (num_q_tiles + 1) / 2 : num_q_tiles);
-    hipLaunchKernelGGL((attn_bwd_dq_kernel<D, CAUSAL, TAIL>), dim3(total), dim3(S::kThreads), 0, stream,
+    hipLaunchKernelGGL((attn_bwd_dq_kernel<D, CAUSAL, TAIL, FUSED>), dim3(total), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
-                       (bf16*)dq, Nq, Nk, num_q_tiles, total, scale, H, Hkv);
+                       (bf16*)dq, Nq, Nk, num_q_tiles, total, scale, H, Hkv, (const bf16*)o, delta_out);
     return hipGetLastError();
 }
 
 template <int D, bool CAUSAL>
 static hipError_t launch_dq_t(const void* q, const void* k, const void* v, const void* d_o,
                               const float* lse, const float* delta, void* dq,
-                              int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
+                              int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream,
+                              const void* o, float* delta_out)
 {
     using S = DqShape<D>;
-    return (Nq != Nk || Nq % S::kTileQ)
-               ? launch_dq_tt<D, CAUSAL, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream)
-               : launch_dq_tt<D, CAUSAL, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream);
+    const bool tail = Nq != Nk || Nq % S::kTileQ;
+    if (o) return tail ? launch_dq_tt<D, CAUSAL, true, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream, o, delta_out)
+                       : launch_dq_tt<D, CAUSAL, false, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream, o, delta_out);
+    return tail ? launch_dq_tt<D, CAUSAL, true, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream, o, delta_out)
+                : launch_dq_tt<D, CAUSAL, false, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream, o, delta_out);
 }
 
+// o != nullptr: Delta is computed from o and d_o inside the kernel and written to delta_out (delta is not read).
 hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
                               const float* lse, const float* delta, void* dq,
-                              int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream)
+                              int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream,
+                              const void* o, float* delta_out)
 {
-    if (D == 128) return causal ? launch_dq_t<128, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream)
-                                : launch_dq_t<128, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream);
-    return causal ? launch_dq_t<64, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream)
-                  : launch_dq_t<64, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream);
+    if (D == 128) return causal ? launch_dq_t<128, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream, o, delta_out)
+                                : launch_dq_t<128, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream, o, delta_out);
+    return causal ? launch_dq_t<64, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream, o, delta_out)
+                  : launch_dq_t<64, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream, o, delta_out);
 }
 
 }  // namespace tk

@@ -227,6 +227,22 @@ int tk_attn_bwd_dq_gqa(const void* q, const void* k, const void* v, const void* 
     return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
 }
 
+int tk_attn_bwd_dq_delta(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+                         const float* lse, float* delta, void* dq,
+                         int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream)
+{
+    if (!q || !k || !v || !o || !d_o || !lse || !delta || !dq) return TK_ERR_NULL_PTR;
+    if (int rc = check_shape(B, Hq, N, D)) return rc;
+    if (int rc = check_heads(Hq, Hkv)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(lse) ||
+        !aligned16(delta) || !aligned16(dq))
+        return TK_ERR_MISALIGNED;
+    if (int rc = check_scale(scale)) return rc;
+    hipError_t e = tk::launch_attn_bwd_dq(q, k, v, d_o, lse, nullptr, dq, B, Hq, Hkv, N, N, D, causal != 0, scale,
+                                          (hipStream_t)stream, o, delta);
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
 int tk_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
                    const float* lse, const float* delta, void* dq,
                    int B, int H, int N, int D, int causal, float scale, void* stream)
@@ -250,13 +266,12 @@ int tk_attn_bwd_rect(const void* q, const void* k, const void* v, const void* o,
 
     hipStream_t s = (hipStream_t)stream;
     float* delta = (float*)workspace;
-    // 1. Delta = rowsum(dO * O), per query head
-    if (tk::launch_attn_bwd_delta(o, d_o, delta, B, Hq, Nq, D, s) != hipSuccess) return TK_ERR_LAUNCH;
-    // 2. dK, dV per key tile of every key/value head
-    if (tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, Nq, Nk, D, causal != 0, scale, s) != hipSuccess)
+    // 1. dQ per query tile; the kernel also forms Delta = rowsum(dO * O) for its rows (each lane holds its
+    //    query's dO row anyway) and leaves it in the workspace, which saves a pass over O and dO
+    if (tk::launch_attn_bwd_dq(q, k, v, d_o, lse, nullptr, dq, B, Hq, Hkv, Nq, Nk, D, causal != 0, scale, s, o, delta) != hipSuccess)
         return TK_ERR_LAUNCH;
-    // 3. dQ per query tile
-    if (tk::launch_attn_bwd_dq(q, k, v, d_o, lse, delta, dq, B, Hq, Hkv, Nq, Nk, D, causal != 0, scale, s) != hipSuccess)
+    // 2. dK, dV per key tile of every key/value head, with that Delta
+    if (tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, Nq, Nk, D, causal != 0, scale, s) != hipSuccess)
         return TK_ERR_LAUNCH;
     return TK_OK;
 }

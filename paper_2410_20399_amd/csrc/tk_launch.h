@@ -36,10 +36,12 @@ hipError_t launch_attn_bwd_dkdv(const void* q, const void* k, const void* v, con
                                 const float* lse, const float* delta, void* dk, void* dv,
                                 int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream);
 
-// dQ (query-tile parallel)
+// dQ (query-tile parallel).  With o != nullptr the kernel computes Delta itself from o and d_o, writes it to
+// delta_out (for the dK/dV kernel launched after it) and does not read delta.
 hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const void* d_o,
                               const float* lse, const float* delta, void* dq,
-                              int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream);
+                              int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream,
+                              const void* o = nullptr, float* delta_out = nullptr);
 
 // bf16 matrix multiply C = A B: A [M,K], B [K,N], C [M,N] row-major; M, N multiples of 256, K of 64
 hipError_t launch_gemm(const void* a, const void* b, void* c, int M, int N, int K, hipStream_t stream);

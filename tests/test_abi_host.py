@@ -126,6 +126,20 @@ def test_stage_entries_reject_bad_arguments(lib):
         assert fn(*([P] * nptr), 1, 1, 128, 96, 0, f(0.125), None) == a.TK_ERR_BAD_DIM
 
 
+def test_dq_delta_entry_rejects_bad_arguments(lib):
+    from paper_2410_20399_amd import attn as a
+    f = ctypes.c_float
+    for i in range(8):
+        ptrs = [P] * 8
+        ptrs[i] = None
+        assert lib.tk_attn_bwd_dq_delta(*ptrs, 1, 4, 2, 128, 64, 1, f(0.125), None) == a.TK_ERR_NULL_PTR
+        ptrs[i] = ODD
+        assert lib.tk_attn_bwd_dq_delta(*ptrs, 1, 4, 2, 128, 64, 1, f(0.125), None) == a.TK_ERR_MISALIGNED
+    assert lib.tk_attn_bwd_dq_delta(*([P] * 8), 1, 4, 3, 128, 64, 1, f(0.125), None) == a.TK_ERR_BAD_DIM
+    assert lib.tk_attn_bwd_dq_delta(*([P] * 8), 1, 4, 2, 0, 64, 1, f(0.125), None) == a.TK_ERR_BAD_DIM
+    assert lib.tk_attn_bwd_dq_delta(*([P] * 8), 1, 4, 2, 128, 64, 1, f(-1.0), None) == a.TK_ERR_BAD_SCALE
+
+
 def test_gqa_entries_reject_bad_arguments(lib):
     from paper_2410_20399_amd import attn as a
     f = ctypes.c_float

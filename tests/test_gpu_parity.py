@@ -157,6 +157,28 @@ def test_delta_stage(attn):
         np.testing.assert_allclose(f64(delta), ref, rtol=0, atol=2e-5)
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,N,D,causal", [(2, 4, 4, 384, 128, True), (1, 6, 2, 300, 64, True), (2, 2, 1, 256, 128, False)])
+def test_dq_stage_with_delta_folded_in(attn, B, Hq, Hkv, N, D, causal):
+    """tk_attn_bwd_dq_delta: the Delta it writes is rowsum(dO * O) of the bf16 O it was given, and its dQ
+    is the dQ of the three-stage form (same products; only Delta's summation order differs)."""
+    g = torch.Generator().manual_seed(9090 + N + D)
+    q, d_o = (torch.randn(B, Hq, N, D, generator=g).to(torch.bfloat16).cuda() for _ in range(2))
+    k, v = (torch.randn(B, Hkv, N, D, generator=g).to(torch.bfloat16).cuda() for _ in range(2))
+    scale = 1 / math.sqrt(D)
+    print(f"launch dq+delta stage B{B} Hq{Hq} Hkv{Hkv} N{N} D{D} causal={causal}", flush=True)
+    o, lse = attn.gqa_fwd(q, k, v, causal, scale)
+    delta = torch.full((B, Hq, N), 77.0, dtype=torch.float32, device="cuda")
+    dq = torch.empty_like(q)
+    assert attn.tk_attn_bwd_dq_delta(q, k, v, o, d_o, lse, delta, dq, B, Hq, Hkv, N, D, causal, scale) == attn.TK_OK
+    delta3 = attn.attn_bwd_delta(o, d_o)
+    dq3 = torch.empty_like(q)
+    assert attn.tk_attn_bwd_dq_gqa(q, k, v, d_o, lse, delta3, dq3, B, Hq, Hkv, N, D, causal, scale) == attn.TK_OK
+    torch.cuda.synchronize()
+    ref = (f64(o.cpu()) * f64(d_o.cpu())).sum(-1)
+    np.testing.assert_allclose(f64(delta.cpu()), ref, rtol=0, atol=2e-5)
+    assert relf(f64(dq.cpu()), f64(dq3.cpu())) <= 1e-3
+
+
 # ------------------------------------------------------------------ degenerate and stress cases
 def test_zero_queries_uniform_attention(attn):
     """Q = 0 -> P uniform: O_i = mean of V (non-causal) or running mean (causal), LSE = ln(#keys)."""
