@@ -187,3 +187,19 @@ def test_bad_arguments():
     with pytest.raises(ValueError):
         orc.rect_bwd(q, k, k, rand(1, 2, 5, 4), False, 0.5)   # dO shape
     orc.rect_fwd(q, k, k, False, 0.5)                    # Nq > Nk is fine without the mask
+
+
+def test_the_pins_tell_end_alignment_from_start_alignment():
+    """The other plausible reading of "causal" for Nq < Nk (query i sees keys j <= i, sequences aligned
+    at their starts) gives different numbers on the same inputs: the tail-of-the-square pin above
+    would reject an oracle that implemented it."""
+    Nq, Nk, D = 4, 9, 5
+    q, k, v = rand(1, 1, Nq, D), rand(1, 1, Nk, D), rand(1, 1, Nk, D)
+    o, lse = orc.rect_fwd(q, k, v, True, 0.4)
+    s = 0.4 * (q[0, 0] @ k[0, 0].T)
+    start_aligned = np.where(np.arange(Nk)[None, :] <= np.arange(Nq)[:, None], s, -np.inf)
+    o_start = softmax(start_aligned, axis=1) @ v[0, 0]
+    assert np.abs(o[0, 0] - o_start).max() > 1e-2
+    end_aligned = np.where(np.arange(Nk)[None, :] <= np.arange(Nq)[:, None] + (Nk - Nq), s, -np.inf)
+    np.testing.assert_allclose(o[0, 0], softmax(end_aligned, axis=1) @ v[0, 0], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(lse[0, 0], logsumexp(end_aligned, axis=1), rtol=0, atol=1e-13)
