@@ -1,13 +1,14 @@
 /*
  * tk_attn.h - C ABI of the MI355X (gfx950) fused exact softmax attention library.
  *
- * The operation is the attention of the paper's Figure 1 (PyTorch listing:
- * softmax(Q K^T) V, softmax in fp32, probabilities cast to bf16 before the
- * second product) with the 1/sqrt(D) temperature that the Appendix B.3
- * listing folds into a base-2 exponent, an optional causal mask, and the
- * per-row log-sum-exp as a second output.  The backward pass is its
- * gradient; the paper reports only its speed (Section 4.1, Table 3), so the
- * algorithm is the chain rule with P recomputed from the saved LSE.
+ * The operation is the attention of the PyTorch listing in the paper's
+ * introduction (its listing figure: softmax(Q K^T) V, softmax in fp32,
+ * probabilities cast to bf16 before the second product) with the 1/sqrt(D)
+ * temperature that the Appendix B.3 listing folds into a base-2 exponent, an
+ * optional causal mask, and the per-row log-sum-exp as a second output.  The
+ * backward pass is its gradient; the paper reports only its speed (the plots
+ * of Section 4.1 and the profile table of Section 4.2), so the algorithm is
+ * the chain rule with P recomputed from the saved LSE.
  *
  * Conventions common to every entry point
  *   - Every tensor pointer is a DEVICE pointer owned by the caller, to
@@ -20,7 +21,10 @@
  *   - causal != 0 masks keys j > i (the diagonal is kept).
  *   - stream is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work: no allocation, no free, no host
- *     synchronisation, no global state.  Outputs are fully overwritten.
+ *     synchronisation.  The only state the library keeps is the compute-unit
+ *     count of each device, queried once (hipGetDevice +
+ *     hipDeviceGetAttribute on the first launch of a persistent kernel on
+ *     that device) and cached.  Outputs are fully overwritten.
  *   - Inputs and outputs must not alias.
  *   - Return value: TK_OK (0) or a negative TK_ERR_* code.  Arguments are
  *     validated on the host before any HIP call is made, so every error
@@ -46,7 +50,7 @@ enum {
 };
 
 /*
- * Forward pass (Figure 1 listing; Appendix B.3 listing for the streaming
+ * Forward pass (the introduction's PyTorch listing; Appendix B.3 listing for the streaming
  * form: running max and sum per query row, base-2 exponent with the folded
  * temperature, rescale of the output accumulator, normalisation at the end).
  *
@@ -94,9 +98,10 @@ int tk_attn_bwd(const void* q, const void* k, const void* v,
 size_t tk_attn_bwd_workspace_bytes(int B, int H, int N, int D);
 
 /*
- * The three stages of tk_attn_bwd as separate calls, so that each kernel's throughput can be
- * measured on its own (tk_attn_bwd runs exactly these, in this order, on one stream).
- * Same pointer, shape and error conventions as above.
+ * The backward pass as three separate stages (Delta, dK/dV, dQ), so that each kernel's throughput
+ * can be measured on its own.  This three-stage form is an equivalent measuring aid: tk_attn_bwd
+ * itself launches tk_attn_bwd_dq_delta (dQ with Delta folded in) followed by tk_attn_bwd_dkdv, see
+ * below.  Same pointer, shape and error conventions as above.
  *
  * Stage 1: Delta_i = sum_d dO_id O_id.
  *   o, d_o : in, bf16 [B,H,N,D];  delta : out, fp32 [B,H,N]

@@ -8,7 +8,7 @@
  * What it computes is the plain definition, one query row (or one key row)
  * at a time, with no tiling, no online softmax and no reordering:
  *
- *   forward  (the PyTorch attention listing of the paper's Figure 1, with
+ *   forward  (the PyTorch attention listing in the introduction's listing figure, with
  *             the 1/sqrt(D) temperature that the Appendix B.3 listing
  *             folds into its exponent, and an optional causal mask):
  *     S_ij   = scale * sum_d Q_id K_jd            (j <= i only, if causal)

@@ -4,7 +4,7 @@ TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the
 benchmark's cpu_baseline leg.  Arrays are numpy float64, row-major, shaped
 [..., N, D]; leading axes are flattened into independent heads.  The
 arithmetic lives in the C file, whose header states the definition it follows
-(paper Figure 1 listing plus the temperature of the Appendix B.3 listing;
+(the PyTorch attention listing in the paper's introduction plus the temperature of the Appendix B.3 listing;
 backward by the chain rule).
 """
 import ctypes

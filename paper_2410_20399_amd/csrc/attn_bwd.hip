@@ -1,6 +1,6 @@
 // Fused exact softmax attention, backward pass, for gfx950 (MI355X).
 //
-// The paper reports the backward kernel's speed only (Section 4.1, Table 3); the algorithm
+// The paper reports the backward kernel's speed only (the attention plots of Section 4.1 and the profile table of Section 4.2); the algorithm
 // here is the chain rule with P recomputed from the saved log-sum-exp:
 //
 //   kernel 1  Delta_i = sum_d dO_id O_id          (HBM stream)
@@ -427,9 +427,10 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
 
         // the block two ahead in the stream (issued two iterations ago) must have landed before the
         // next iteration reads its rows; the newer prefetches may stay in flight (wave 0 issues one
-        // more load per block)
-        if (wave == 0) wait_vmcnt<(S::kAhead - 2) * (S::kLoadsPerBlock + 1)>();
-        else wait_vmcnt<(S::kAhead - 2) * S::kLoadsPerBlock>();
+        // more load per block).  The wave's own LDS reads of this block's stage must have returned as
+        // well: after the barrier the next step's prefetch overwrites that stage.
+        if (wave == 0) wait_vmcnt_lds_done<(S::kAhead - 2) * (S::kLoadsPerBlock + 1)>();
+        else wait_vmcnt_lds_done<(S::kAhead - 2) * S::kLoadsPerBlock>();
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);

@@ -32,11 +32,18 @@ size_t delta_bytes(int B, int H, int N)
     return (b + 255) & ~(size_t)255;
 }
 
-// query and key lengths of one call; the causal mask aligns the sequences at their ends and needs Nq <= Nk
-int check_lengths(int B, int H, int Nq, int Nk, int D, int causal)
+int check_heads(int H, int Hkv)
 {
-    if (int rc = check_shape(B, H, Nq, D)) return rc;
-    if (int rc = check_shape(B, H, Nk, D)) return rc;
+    return (Hkv >= 1 && Hkv <= H && H % Hkv == 0) ? TK_OK : TK_ERR_BAD_DIM;
+}
+
+// Head counts and lengths of one call: the query side is [B, Hq, Nq, D], the key side [B, Hkv, Nk, D], and
+// each is bounded by its own extent; the causal mask aligns the sequences at their ends and needs Nq <= Nk.
+int check_lengths(int B, int Hq, int Hkv, int Nq, int Nk, int D, int causal)
+{
+    if (int rc = check_heads(Hq, Hkv)) return rc;
+    if (int rc = check_shape(B, Hq, Nq, D)) return rc;
+    if (int rc = check_shape(B, Hkv, Nk, D)) return rc;
     if (causal && Nq > Nk) return TK_ERR_BAD_DIM;
     return TK_OK;
 }
@@ -87,11 +94,6 @@ DecodePlan plan_decode(int B, int Hq, int Hkv, int Nk, int compute_units)
     return p;
 }
 
-int check_heads(int H, int Hkv)
-{
-    return (Hkv >= 1 && Hkv <= H && H % Hkv == 0) ? TK_OK : TK_ERR_BAD_DIM;
-}
-
 }  // namespace
 
 extern "C" {
@@ -100,8 +102,7 @@ int tk_attn_fwd_rect(const void* q, const void* k, const void* v, void* o, float
                      int B, int Hq, int Hkv, int Nq, int Nk, int D, int causal, float scale, void* stream)
 {
     if (!q || !k || !v || !o || !lse) return TK_ERR_NULL_PTR;
-    if (int rc = check_lengths(B, Hq, Nq, Nk, D, causal)) return rc;
-    if (int rc = check_heads(Hq, Hkv)) return rc;
+    if (int rc = check_lengths(B, Hq, Hkv, Nq, Nk, D, causal)) return rc;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return TK_ERR_MISALIGNED;
     if (int rc = check_scale(scale)) return rc;
     hipError_t e = tk::launch_attn_fwd(q, k, v, o, lse, B, Hq, Hkv, Nq, Nk, D, causal != 0, scale, (hipStream_t)stream);
@@ -123,8 +124,7 @@ int tk_attn_fwd(const void* q, const void* k, const void* v, void* o, float* lse
 int tk_attn_decode_plan(int B, int Hq, int Hkv, int Nk, int D, int compute_units, int* plan)
 {
     if (!plan) return TK_ERR_NULL_PTR;
-    if (int rc = check_shape(B, Hq, Nk, D)) return rc;
-    if (int rc = check_heads(Hq, Hkv)) return rc;
+    if (int rc = check_lengths(B, Hq, Hkv, 1, Nk, D, 0)) return rc;
     if (compute_units < 1) return TK_ERR_BAD_DIM;
     const DecodePlan p = plan_decode(B, Hq, Hkv, Nk, compute_units);
     plan[0] = p.b * p.h;
@@ -137,7 +137,7 @@ int tk_attn_decode_plan(int B, int Hq, int Hkv, int Nk, int D, int compute_units
 
 size_t tk_attn_decode_workspace_bytes(int B, int Hq, int Hkv, int Nk, int D)
 {
-    if (check_shape(B, Hq, Nk, D) != TK_OK || check_heads(Hq, Hkv) != TK_OK) return 0;
+    if (check_lengths(B, Hq, Hkv, 1, Nk, D, 0) != TK_OK) return 0;
     // partial O (fp32 [splits][B*Hq][D]) and partial LSE (fp32 [splits][B*Hq]), each padded to 256 bytes
     const size_t rows = (size_t)B * Hq, splits = (size_t)decode_max_splits(B, Hq, Hkv);
     const size_t o_bytes = (splits * rows * D * sizeof(float) + 255) & ~(size_t)255;
@@ -150,8 +150,7 @@ int tk_attn_decode(const void* q, const void* k, const void* v, void* o, float* 
                    void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!q || !k || !v || !o || !lse || !workspace) return TK_ERR_NULL_PTR;
-    if (int rc = check_shape(B, Hq, Nk, D)) return rc;
-    if (int rc = check_heads(Hq, Hkv)) return rc;
+    if (int rc = check_lengths(B, Hq, Hkv, 1, Nk, D, 0)) return rc;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(workspace))
         return TK_ERR_MISALIGNED;
     if (int rc = check_scale(scale)) return rc;
@@ -256,8 +255,7 @@ int tk_attn_bwd_rect(const void* q, const void* k, const void* v, const void* o,
                      void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !workspace) return TK_ERR_NULL_PTR;
-    if (int rc = check_lengths(B, Hq, Nq, Nk, D, causal)) return rc;
-    if (int rc = check_heads(Hq, Hkv)) return rc;
+    if (int rc = check_lengths(B, Hq, Hkv, Nq, Nk, D, causal)) return rc;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(lse) ||
         !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(workspace))
         return TK_ERR_MISALIGNED;

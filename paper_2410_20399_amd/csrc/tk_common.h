@@ -40,6 +40,14 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// s_waitcnt vmcnt(n) lgkmcnt(0): additionally every LDS read of this wave has returned.  Used before a
+// barrier after which another wave's direct-to-LDS load may overwrite what this wave was reading.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_lds_done() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14));
+}
+
 // 16 bytes per lane straight from global memory into LDS; lds_wave_base must be wave-uniform.
 __device__ __forceinline__ void load_global_to_lds16(const void* gptr, char* lds_wave_base) {
     __builtin_amdgcn_global_load_lds(gptr, (TK_LDS uint32_t*)lds_wave_base, 16, 0, 0);

@@ -3,14 +3,25 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 
+#include <atomic>
+
 namespace tk {
 
-// Compute units of the current device (persistent kernels size their grid by it).
+// Compute units of the current device (persistent kernels size their grid by it).  The attribute is
+// queried once per device and cached; a launch then costs one hipGetDevice (a thread-local read).
 inline hipError_t compute_unit_count(int* cus) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cache[kMaxDevices];      // 0 = not queried yet
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    return hipDeviceGetAttribute(cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (dev >= 0 && dev < kMaxDevices) {
+        const int hit = cache[dev].load(std::memory_order_relaxed);
+        if (hit > 0) { *cus = hit; return hipSuccess; }
+    }
+    e = hipDeviceGetAttribute(cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess && dev >= 0 && dev < kMaxDevices) cache[dev].store(*cus, std::memory_order_relaxed);
+    return e;
 }
 
 // H query heads share Hkv key/value heads in groups of H / Hkv consecutive heads (Hkv == H: plain

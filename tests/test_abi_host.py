@@ -212,6 +212,11 @@ def test_decode_entry_rejects_bad_arguments(lib):
     assert decode(ws_bytes=need - 1) == a.TK_ERR_WORKSPACE_TOO_SMALL
     assert lib.tk_attn_decode_workspace_bytes(2, 8, 3, 1000, 128) == 0
     assert lib.tk_attn_decode_workspace_bytes(2, 8, 2, 0, 128) == 0
+    # K and V are [B, Hkv, Nk, D]: a long grouped history is bounded by B*Hkv*Nk, not B*Hq*Nk
+    assert lib.tk_attn_decode_workspace_bytes(700, 512, 8, 100000, 128) > 0
+    assert a.tk_attn_decode_plan(700, 512, 8, 100000, 128, 256)[0] == a.TK_OK
+    # ... and a key side that really is too large is still rejected
+    assert lib.tk_attn_decode_workspace_bytes(700, 512, 512, 100000, 128) == 0
 
 
 def test_decode_plan_invariants(lib):
@@ -223,7 +228,7 @@ def test_decode_plan_invariants(lib):
             (1, 2, 16, 300), ((1, 1), (8, 8), (32, 8), (128, 1), (129, 1), (256, 2)),
             (1, 63, 64, 65, 255, 256, 1000, 8192, 100000, 1 << 20), (64, 128), (1, 64, 256, 304)):
         rc, (heads, rows, splits, per, max_splits) = a.tk_attn_decode_plan(B, Hq, Hkv, Nk, D, cus)
-        if B * Hq * Nk > 0x7fffffff * 16:                 # beyond what any entry point accepts
+        if B * Hkv * Nk > 0x7fffffff * 16:                # beyond what any entry point accepts (K, V are [B,Hkv,Nk,D])
             assert rc == a.TK_ERR_BAD_DIM
             continue
         assert rc == a.TK_OK

@@ -9,6 +9,7 @@ import pytest
 import torch
 
 from oracle import attn_oracle as orc
+from grad_check import check_grad
 
 pytestmark = pytest.mark.gpu
 
@@ -66,11 +67,8 @@ def test_gqa_forward_backward(attn, B, Hq, Hkv, N, D, causal):
     for name, g, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
         g = f64(g.cpu())
         assert g.shape == r.shape, name
-        assert np.isfinite(g).all(), name
         assert relf(g, r) <= GRAD_RELF, (name, relf(g, r))
-        for b in range(g.shape[0]):
-            for h in range(g.shape[1]):
-                assert relf(g[b, h], r[b, h]) <= GRAD_RELF, (name, b, h)
+        check_grad(g, r, name)      # every head, every 32-row block, every element
 
 
 def test_gqa_with_one_head_per_group_is_the_multi_head_call(attn):
@@ -108,6 +106,6 @@ def test_gqa_full_size_sampled(attn):
     assert eo.max() <= O_MAX and eo.mean() <= O_MEAN
     assert np.abs(f64(lse[b:b + 1, hs].cpu()) - lse_ref).max() <= LSE_MAX
     rq, rk, rv = orc.gqa_bwd(qs, ks, vs, dos, causal, scale)
-    assert relf(f64(dq[b:b + 1, hs].cpu()), rq) <= GRAD_RELF
-    assert relf(f64(dk[b:b + 1, hk:hk + 1].cpu()), rk) <= GRAD_RELF
-    assert relf(f64(dv[b:b + 1, hk:hk + 1].cpu()), rv) <= GRAD_RELF
+    check_grad(f64(dq[b:b + 1, hs].cpu()), rq, "dq")
+    check_grad(f64(dk[b:b + 1, hk:hk + 1].cpu()), rk, "dk")
+    check_grad(f64(dv[b:b + 1, hk:hk + 1].cpu()), rv, "dv")

@@ -3,7 +3,10 @@
 Tolerances (from the benchmark spec, checked against the UNROUNDED fp64 oracle):
   O   : max-abs <= 2e-2 and mean-abs <= 2e-3
   LSE : max-abs <= 1e-3
-  dQ, dK, dV : relative Frobenius error <= 3e-2
+  dQ, dK, dV : relative Frobenius error <= 3e-2, per head AND per 32-row block, plus an element-wise
+               bound (tests/grad_check.py), so that a wrong row, block or tail cannot hide in a norm
+At full size the oracle checks sampled heads; every other head is tied to them by a bit-for-bit
+comparison of the batched launch with the same head run alone.
 """
 import math
 
@@ -13,6 +16,7 @@ import torch
 
 from paper_2410_20399_amd import workloads
 from oracle import attn_oracle as orc
+from grad_check import check_grad
 
 pytestmark = pytest.mark.gpu
 
@@ -69,12 +73,8 @@ def test_small_forward_backward(attn, B, H, N, D, causal):
     rq, rk, rv = orc.attn_bwd(f64(q), f64(k), f64(v), f64(d_o), causal, scale)
     for name, g, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
         g = f64(g.cpu())
-        assert np.isfinite(g).all(), name
-        # whole tensor and every head separately
         assert relf(g, r) <= GRAD_RELF, (name, relf(g, r))
-        for b in range(B):
-            for h in range(H):
-                assert relf(g[b, h], r[b, h]) <= GRAD_RELF, (name, b, h)
+        check_grad(g, r, name)      # every head, every 32-row block, every element
 
 
 def test_config1_exact_workload(attn):
@@ -140,8 +140,34 @@ def test_full_size_backward_sampled_heads(attn, idx, n_heads):
         print(f"  oracle head ({b},{h})", flush=True)
         rq, rk, rv = orc.attn_bwd(f64(q[b, h]), f64(k[b, h]), f64(v[b, h]), f64(d_o[b, h]), w.causal, w.scale)
         for name, g, r in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
-            e = relf(f64(g[b, h]), r)
-            assert e <= GRAD_RELF, (w.name, name, b, h, e)
+            check_grad(f64(g[b, h]), r, (w.name, name, b, h))
+
+
+@pytest.mark.parametrize("idx", [4, 5, 6])
+def test_full_size_every_head_equals_the_head_run_alone(attn, idx):
+    """Completeness at full size.  Every kernel computes a head in an order that does not depend on
+    where the head sits in the launch, so O, LSE, dQ, dK, dV of head (b, h) of the batched call must be
+    bit-identical to a B = 1, H = 1 call on that head alone.  With the oracle check of the sampled heads
+    above this covers all heads, whichever persistent workgroup, pass or position served them."""
+    w = workloads.WORKLOADS[idx]
+    q, k, v, d_o = workloads.make_inputs(w)
+    print(f"launch fwd+bwd {w.name} batched", flush=True)
+    qd, kd, vd, dod = (t.cuda() for t in (q, k, v, d_o))
+    o, lse = attn.attn_fwd(qd, kd, vd, w.causal, w.scale)
+    dq, dk, dv = attn.attn_bwd(qd, kd, vd, o, dod, lse, w.causal, w.scale)
+    torch.cuda.synchronize()
+    ws1 = attn.alloc_bwd_workspace(1, 1, w.N, w.D)
+    print(f"launch {w.B * w.H} single-head calls", flush=True)
+    bad = []
+    for b in range(w.B):
+        for h in range(w.H):
+            one = lambda t: t[b:b + 1, h:h + 1]           # contiguous [1,1,N,D] views of the batched tensors
+            o1, lse1 = attn.attn_fwd(one(qd), one(kd), one(vd), w.causal, w.scale)
+            g1 = attn.attn_bwd(one(qd), one(kd), one(vd), one(o), one(dod), one(lse), w.causal, w.scale, workspace=ws1)
+            same = [torch.equal(o1, one(o)), torch.equal(lse1, one(lse))] + [torch.equal(a, one(t)) for a, t in zip(g1, (dq, dk, dv))]
+            if not all(same):
+                bad.append((b, h, same))
+    assert not bad, bad[:8]
 
 
 # ------------------------------------------------------------------ Delta stage on its own
@@ -219,6 +245,8 @@ def test_large_scores_stay_finite(attn):
         assert np.abs(f64(lse.cpu()) - lse_ref).max() <= LSE_MAX * 4
         rq, rk, rv = orc.attn_bwd(f64(q), f64(k), f64(v), f64(d_o), causal, scale)
         for g, r in ((dq, rq), (dk, rk), (dv, rv)):
+            # (whole-tensor norm only: P is nearly one-hot here, dP - Delta cancels almost completely at
+            # the selected key, and what is left of single rows is mostly the rounding of Delta)
             assert relf(f64(g.cpu()), r) <= GRAD_RELF
 
 
@@ -234,7 +262,7 @@ def test_nonstandard_scale(attn):
         check_forward(o, lse, o_ref, lse_ref, ("scale", scale))
         rq, rk, rv = orc.attn_bwd(f64(q), f64(k), f64(v), f64(d_o), True, scale)
         for g, r in ((dq, rq), (dk, rk), (dv, rv)):
-            assert relf(f64(g.cpu()), r) <= GRAD_RELF
+            check_grad(f64(g.cpu()), r, ("scale", scale))
 
 
 def test_reproducibility(attn):
@@ -268,7 +296,7 @@ def test_runs_on_side_stream_and_reuses_workspace(attn):
     rq, rk, rv = orc.attn_bwd(f64(q), f64(k), f64(v), f64(d_o), False, 0.125)
     for g in (g1, g2):
         for t, r in zip(g, (rq, rk, rv)):
-            assert relf(f64(t.cpu()), r) <= GRAD_RELF
+            check_grad(f64(t.cpu()), r, "side stream")
 
 
 def test_tensors_beyond_two_to_the_31_elements(attn):
@@ -295,7 +323,7 @@ def test_tensors_beyond_two_to_the_31_elements(attn):
         o_ref, lse_ref = orc.attn_fwd(qs, ks, vs, causal, scale)
         check_forward(o[b, h][None], lse[b, h][None], o_ref, lse_ref, (b, h))
         for name, g, r in zip(("dq", "dk", "dv"), (dq, dk, dv), orc.attn_bwd(qs, ks, vs, dos, causal, scale)):
-            assert relf(f64(g[b, h].cpu())[None], r) <= GRAD_RELF, (name, b, h)
+            check_grad(f64(g[b, h].cpu())[None], r, (name, b, h))
     # no head was skipped: the sentinel survives nowhere (sampled: the last rows of a spread of heads)
     for t in (o, dq, dk, dv):
         flat = t.view(B * H, N, D)[:: 997, -1]

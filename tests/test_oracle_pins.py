@@ -2,7 +2,7 @@
 
 Every check compares oracle/attn_oracle.c with something that is not the
 oracle: a brute-force numpy softmax without max subtraction, closed forms,
-algebraic invariants of the definition (paper Figure 1 listing + the
+algebraic invariants of the definition (the PyTorch attention listing in the paper's introduction + the
 temperature of the Appendix B.3 listing), constants the paper prints, and
 central finite differences of a brute-force forward for the gradients.
 """
