@@ -46,7 +46,8 @@ enum {
     TK_ERR_MISALIGNED = -3,          /* a tensor pointer is not 16-byte aligned */
     TK_ERR_BAD_SCALE = -4,           /* scale is not finite or not > 0 */
     TK_ERR_WORKSPACE_TOO_SMALL = -5, /* workspace_bytes < tk_attn_bwd_workspace_bytes(...) */
-    TK_ERR_LAUNCH = -6               /* hipGetLastError() reported a failure after a launch */
+    TK_ERR_LAUNCH = -6,              /* hipGetLastError() reported a failure after a launch */
+    TK_ERR_SCRATCH_LIMIT = -7        /* tk_attn_bwd_noalloc: B*H*N exceeds tk_attn_bwd_noalloc_max_rows() */
 };
 
 /*
@@ -96,6 +97,27 @@ int tk_attn_bwd(const void* q, const void* k, const void* v,
 
 /* Bytes of workspace tk_attn_bwd needs for this shape; 0 if the shape is invalid. */
 size_t tk_attn_bwd_workspace_bytes(int B, int H, int N, int D);
+
+/*
+ * tk_attn_bwd for callers that cannot allocate device memory and have no workspace to hand over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs,
+ * kernels and results (bit for bit) as tk_attn_bwd with a minimal workspace, but Delta lives in a scratch
+ * array that is part of the library's device image: 4 MiB per GPU the library runs on, held until the
+ * process ends.  The call allocates and frees nothing, on the host or on the device; its first use on a
+ * device looks the array's address up (hipGetSymbolAddress) and keeps it.
+ *   Limit: B*H*N <= tk_attn_bwd_noalloc_max_rows() (1,048,576), else TK_ERR_SCRATCH_LIMIT.
+ *   Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (different
+ *   streams, or different threads) race on it and must be serialised by the caller.  Nothing in it
+ *   needs clearing between calls (the first kernel writes every Delta the second one reads).
+ * Other errors as tk_attn_bwd.
+ */
+int tk_attn_bwd_noalloc(const void* q, const void* k, const void* v,
+                        const void* o, const void* d_o, const float* lse,
+                        void* dq, void* dk, void* dv,
+                        int B, int H, int N, int D, int causal, float scale,
+                        void* stream);
+
+size_t tk_attn_bwd_noalloc_max_rows(void);
 
 /*
  * The backward pass as three separate stages (Delta, dK/dV, dQ), so that each kernel's throughput

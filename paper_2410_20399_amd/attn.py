@@ -20,11 +20,12 @@ TK_ERR_MISALIGNED = -3
 TK_ERR_BAD_SCALE = -4
 TK_ERR_WORKSPACE_TOO_SMALL = -5
 TK_ERR_LAUNCH = -6
+TK_ERR_SCRATCH_LIMIT = -7
 
 EXPORTS = ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
            "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_attn_fwd_gqa", "tk_attn_bwd_gqa", "tk_attn_bwd_dkdv_gqa",
            "tk_attn_bwd_dq_gqa", "tk_attn_bwd_dq_delta", "tk_attn_fwd_rect", "tk_attn_bwd_rect", "tk_attn_decode",
-           "tk_attn_decode_workspace_bytes", "tk_attn_decode_plan", "tk_rotary", "tk_gemm", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
+           "tk_attn_decode_workspace_bytes", "tk_attn_decode_plan", "tk_attn_bwd_noalloc", "tk_attn_bwd_noalloc_max_rows", "tk_rotary", "tk_gemm", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
 
 _lib = None
 
@@ -50,6 +51,10 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.tk_attn_fwd.restype = i
     lib.tk_attn_bwd.argtypes = [vp, vp, vp, vp, vp, fp, vp, vp, vp, i, i, i, i, i, f, vp, sz, vp]
     lib.tk_attn_bwd.restype = i
+    lib.tk_attn_bwd_noalloc.argtypes = [vp, vp, vp, vp, vp, fp, vp, vp, vp, i, i, i, i, i, f, vp]
+    lib.tk_attn_bwd_noalloc.restype = i
+    lib.tk_attn_bwd_noalloc_max_rows.argtypes = []
+    lib.tk_attn_bwd_noalloc_max_rows.restype = sz
     lib.tk_attn_bwd_workspace_bytes.argtypes = [i, i, i, i]
     lib.tk_attn_bwd_workspace_bytes.restype = sz
     lib.tk_attn_bwd_delta.argtypes = [vp, vp, fp, i, i, i, i, vp]
@@ -133,6 +138,16 @@ def tk_attn_bwd(q, k, v, o, d_o, lse, dq, dk, dv, B, H, N, D, causal, scale,
     return load_library().tk_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse),
                                       _ptr(dq), _ptr(dk), _ptr(dv), B, H, N, D, int(bool(causal)),
                                       float(scale), _ptr(workspace), int(workspace_bytes), _stream(stream))
+
+
+def tk_attn_bwd_noalloc(q, k, v, o, d_o, lse, dq, dk, dv, B, H, N, D, causal, scale, stream=None) -> int:
+    return load_library().tk_attn_bwd_noalloc(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(d_o), _ptr(lse),
+                                              _ptr(dq), _ptr(dk), _ptr(dv), B, H, N, D, int(bool(causal)),
+                                              float(scale), _stream(stream))
+
+
+def tk_attn_bwd_noalloc_max_rows() -> int:
+    return int(load_library().tk_attn_bwd_noalloc_max_rows())
 
 
 def tk_attn_bwd_workspace_bytes(B, H, N, D) -> int:

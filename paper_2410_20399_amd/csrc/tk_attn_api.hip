@@ -5,6 +5,14 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <atomic>
+
+// Scratch of tk_attn_bwd_noalloc: Delta (fp32, one value per query row) for callers that cannot hand over a
+// workspace.  One copy per GPU, held until the process ends.  In host code this name is only a stand-in
+// for the symbol; the device address comes from hipGetSymbolAddress (noalloc_scratch() below).
+constexpr size_t kNoallocScratchFloats = (size_t)1 << 20;      // 4 MiB: B*H*N <= 1,048,576 query rows
+static __device__ __align__(256) float g_noalloc_scratch[kNoallocScratchFloats];
+
 namespace {
 
 constexpr int kTileN = 128;      // rows per workgroup tile (sequences are padded to it inside the kernels)
@@ -19,6 +27,24 @@ int check_shape(int B, int H, int N, int D)
     if (tiles > 0x7fffffffLL) return TK_ERR_BAD_DIM;
     if ((long long)B * H * N > 0x7fffffffLL * 16) return TK_ERR_BAD_DIM;   // row indices stay far inside 64 bits
     return TK_OK;
+}
+
+// Device address of g_noalloc_scratch on the current device, looked up once per device (with that device
+// current, as it is here: the caller's stream belongs to it) and kept.  Every GPU holds its own copy of the
+// array at its own address.  nullptr if the lookup fails.
+float* noalloc_scratch()
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<float*> ptr[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    float* p = ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(g_noalloc_scratch)) != hipSuccess || !sym) return nullptr;
+    p = (float*)sym;
+    ptr[dev].store(p, std::memory_order_release);      // (two threads racing here store the same address)
+    return p;
 }
 
 int check_scale(float scale)
@@ -292,6 +318,31 @@ int tk_attn_bwd(const void* q, const void* k, const void* v, const void* o, cons
                            workspace, workspace_bytes, stream);
 }
 
+int tk_attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse,
+                        void* dq, void* dk, void* dv,
+                        int B, int H, int N, int D, int causal, float scale, void* stream)
+{
+    if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv) return TK_ERR_NULL_PTR;
+    if (int rc = check_lengths(B, H, H, N, N, D, causal)) return rc;
+    if ((size_t)B * H * N > kNoallocScratchFloats) return TK_ERR_SCRATCH_LIMIT;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(lse) ||
+        !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
+        return TK_ERR_MISALIGNED;
+    if (int rc = check_scale(scale)) return rc;
+    float* delta = noalloc_scratch();       // a pointer, never the array's name: that is not a device address in host code
+    if (!delta) return TK_ERR_LAUNCH;
+    hipStream_t s = (hipStream_t)stream;
+    // the same two kernels as tk_attn_bwd in its small-workspace form; Delta is written in full by the first
+    // before the second reads it, so nothing in the scratch has to be cleared
+    if (tk::launch_attn_bwd_dq(q, k, v, d_o, lse, nullptr, dq, B, H, H, N, N, D, causal != 0, scale, s, o, delta) != hipSuccess)
+        return TK_ERR_LAUNCH;
+    if (tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, H, H, N, N, D, causal != 0, scale, s) != hipSuccess)
+        return TK_ERR_LAUNCH;
+    return TK_OK;
+}
+
+size_t tk_attn_bwd_noalloc_max_rows(void) { return kNoallocScratchFloats; }
+
 int tk_gemm(const void* a, const void* b, void* c, int M, int N, int K, void* stream)
 {
     if (!a || !b || !c) return TK_ERR_NULL_PTR;
@@ -331,6 +382,7 @@ const char* tk_status_string(int status)
         case TK_ERR_BAD_SCALE: return "scale must be finite and > 0";
         case TK_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case TK_ERR_LAUNCH: return "kernel launch failed";
+        case TK_ERR_SCRATCH_LIMIT: return "B*H*N exceeds the built-in scratch of tk_attn_bwd_noalloc (use tk_attn_bwd with a workspace)";
         default: return "unknown status";
     }
 }

@@ -42,11 +42,11 @@ def test_version_and_status_strings(lib):
     from paper_2410_20399_amd import attn
     assert attn.version() >= 100
     seen = set()
-    for code in range(0, -7, -1):
+    for code in range(0, -8, -1):
         s = attn.status_string(code)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 7
+    assert len(seen) == 8
     assert attn.status_string(-99) == "unknown status"
 
 
@@ -246,6 +246,32 @@ def test_decode_plan_invariants(lib):
     assert a.tk_attn_decode_plan(1, 8, 3, 100, 64, 256)[0] == a.TK_ERR_BAD_DIM
     assert a.tk_attn_decode_plan(1, 8, 2, 100, 64, 0)[0] == a.TK_ERR_BAD_DIM
     assert lib.tk_attn_decode_plan(1, 8, 2, 100, 64, 256, None) == a.TK_ERR_NULL_PTR
+
+
+def test_noalloc_backward_rejects_bad_arguments(lib):
+    """Validation comes before the scratch lookup and every HIP call, so it runs without a GPU."""
+    from paper_2410_20399_amd import attn as a
+    f = ctypes.c_float
+
+    def call(ptrs=None, B=1, H=1, N=128, D=64, causal=0, scale=0.125):
+        ptrs = ptrs or [P] * 9
+        return lib.tk_attn_bwd_noalloc(*ptrs, B, H, N, D, causal, f(scale), None)
+
+    for i in range(9):
+        ptrs = [P] * 9
+        ptrs[i] = None
+        assert call(ptrs) == a.TK_ERR_NULL_PTR
+    ptrs = [P] * 9
+    ptrs[6] = ODD
+    assert call(ptrs) == a.TK_ERR_MISALIGNED
+    assert call(D=96) == a.TK_ERR_BAD_DIM
+    assert call(N=0) == a.TK_ERR_BAD_DIM
+    assert call(scale=0.0) == a.TK_ERR_BAD_SCALE
+    limit = a.tk_attn_bwd_noalloc_max_rows()
+    assert limit == 1 << 20
+    assert call(B=16, H=16, N=4097) == a.TK_ERR_SCRATCH_LIMIT          # one row per head too many
+    assert call(B=1, H=1, N=limit + 1) == a.TK_ERR_SCRATCH_LIMIT
+    assert "scratch" in a.status_string(a.TK_ERR_SCRATCH_LIMIT)
 
 
 def test_gemm_rejects_bad_arguments(lib):
