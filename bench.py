@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (published: 2.5 PFLOP/s)
 # reads in the same run; the files under profiles/ give the commands and the raw counters).  The
 # live run cannot collect counters itself, so other workloads report null.
 MEASURED_TRAFFIC = {
-    "fwdbwd_causal_b16_h16_n4096_d128": {"kernel": "attn_bwd_dkdv_kernel", "bytes": 1.245e9 + 0.537e9,
+    "fwdbwd_causal_b16_h16_n4096_d128/recompute": {"kernel": "attn_bwd_dkdv_kernel", "bytes": 1.245e9 + 0.537e9,
                                          "source": "profiles/bench_fwdbwd_causal_b16_h16_n4096_d128.txt"},
     "gemm_8192x8192x8192": {"kernel": "gemm_kernel", "bytes": 1.61e9 + 0.148e9, "source": "profiles/gemm_8192x8192x8192.txt"},
     "decode_b16_hq32_hkv8_nk8192_d128": {"kernel": "attn_fwd_kernel", "bytes": 537.2e6 + 0.54e6, "source": "profiles/decode_b16_hq32_hkv8_nk8192_d128.txt"},
@@ -225,6 +225,9 @@ def main():
     ap.add_argument("--op", choices=["attention", "rotary", "gemm", "decode"], default="attention",
                     help="attention (default: the headline fwd+bwd step), the rotary kernel on the same tensor shape, "
                          "the bf16 GEMM (8192^3), or the decode-shaped forward (one query per head, B16 Hq32 Hkv8 Nk8192 D128)")
+    ap.add_argument("--bwd-form", choices=["spill", "recompute"], default="spill",
+                    help="spill (default): tk_attn_bwd gets the large workspace, its dK/dV kernel stores dS and dQ is formed "
+                         "from it (Delta, dK/dV, dQ-from-dS kernels); recompute: Delta-only workspace, dQ kernel recomputes dS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle sample")
     ap.add_argument("--no-mfma-probe", action="store_true", help="skip the bare-MFMA ceiling measurement")
@@ -259,9 +262,12 @@ def main():
     o = torch.empty_like(qd)
     lse = torch.empty((B, H, N), dtype=torch.float32, device=dev)
     dq, dk, dv = torch.empty_like(qd), torch.empty_like(kd), torch.empty_like(vd)
-    ws = attn.alloc_bwd_workspace(B, H, N, D, dev)
+    spill = args.bwd_form == "spill"
+    ws = attn.alloc_bwd_workspace(B, H, N, D, dev, spill=spill)     # allocated once, outside every timed region
     ws_bytes = ws.numel()
-    delta = ws[:B * H * N * 4].view(torch.float32)      # the workspace is exactly the Delta array
+    delta = ws[:B * H * N * 4].view(torch.float32)      # the workspace starts with the Delta array
+    delta_pad = (B * H * N * 4 + 255) & ~255
+    ds = ws[delta_pad:] if spill else None              # ... followed by the dS blocks in the spill form
     stream = torch.cuda.current_stream()
 
     def check(rc, what):
@@ -302,15 +308,24 @@ def main():
 
     # ---- per-kernel durations: the same kernels through the stage entry points, HIP events on the launch stream
 
-    # the backward runs two kernels: dQ with Delta folded in, then dK/dV; the stand-alone Delta pass
-    # (tk_attn_bwd_delta, an HBM stream over O and dO) is timed too, as the HBM-bound reference point
+    # recompute form: the backward runs two kernels: dQ with Delta folded in, then dK/dV; the stand-alone Delta
+    # pass (tk_attn_bwd_delta, an HBM stream over O and dO) is timed too, as the HBM-bound reference point.
+    # spill form: three kernels: Delta, dK/dV storing dS, dQ from the stored dS.
     dq_delta_call = lambda: attn.tk_attn_bwd_dq_delta(qd, kd, vd, o, dod, lse, delta, dq, B, H, Hkv, N, D, w.causal, w.scale, stream)
+    delta_call = lambda: attn.tk_attn_bwd_delta(o, dod, delta, B, H, N, D, stream)
     stages = [("attn_fwd_kernel", lambda: check(fwd_call(), "fwd"))]
-    if w.backward:
+    if w.backward and spill:
+        stages += [
+            ("attn_bwd_delta_kernel", lambda: check(delta_call(), "delta")),
+            ("attn_bwd_dkdv_kernel", lambda: check(attn.tk_attn_bwd_dkdv_ds(qd, kd, vd, dod, lse, delta, dk, dv, ds, B, H, Hkv, N, D,
+                                                                            w.causal, w.scale, stream), "dkdv+ds")),
+            ("attn_bwd_dq_from_ds_kernel", lambda: check(attn.tk_attn_bwd_dq_from_ds(kd, ds, dq, B, H, Hkv, N, D, w.causal, w.scale, stream), "dq from ds")),
+        ]
+    elif w.backward:
         stages += [
             ("attn_bwd_dq_kernel", lambda: check(dq_delta_call(), "dq+delta")),
             ("attn_bwd_dkdv_kernel", lambda: check(dkdv_call(), "dkdv")),
-            ("attn_bwd_delta_kernel", lambda: check(attn.tk_attn_bwd_delta(o, dod, delta, B, H, N, D, stream), "delta")),
+            ("attn_bwd_delta_kernel", lambda: check(delta_call(), "delta")),
         ]
     kernel_ms = {name: 0.0 for name, _ in stages}
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(stages) + 1)] for _ in range(args.steps)]
@@ -332,6 +347,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": B, "H": H, "Hkv": Hkv, "N": N, "D": D, "causal": w.causal,
                    "pass": "fwd+bwd" if w.backward else "fwd",
+                   **({"bwd_form": args.bwd_form, "bwd_workspace_bytes": ws_bytes} if w.backward else {}),
                    "flop_convention": "fwd 4*B*H*N^2*D, bwd 2.5x fwd, halved when causal"},
         "frac_of_mfma_peak": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
         "fwd": {"ms": round(kernel_ms["attn_fwd_kernel"], 4), "tflops": round(fwd_tflops, 2),
@@ -339,13 +355,15 @@ def main():
         "kernel_ms": {k_: round(v_, 4) for k_, v_ in kernel_ms.items()},
     }
     if w.backward:
-        bwd_ms = kernel_ms["attn_bwd_dq_kernel"] + kernel_ms["attn_bwd_dkdv_kernel"]       # what tk_attn_bwd launches
+        # what tk_attn_bwd launches in this form
+        dq_name = "attn_bwd_dq_from_ds_kernel" if spill else "attn_bwd_dq_kernel"
+        bwd_ms = kernel_ms[dq_name] + kernel_ms["attn_bwd_dkdv_kernel"] + (kernel_ms["attn_bwd_delta_kernel"] if spill else 0.0)
         bwd_tflops = flops_bwd / (bwd_ms * 1e-3) / 1e12
-        # the dK/dV kernel executes four of the backward's five products
-        # (S, dP, dV, dK: 8*D flops per kept query-key pair); the dQ kernel three (S, dP, dQ: 6*D)
+        # the dK/dV kernel executes four of the backward's five products (S, dP, dV, dK: 8*D flops per kept
+        # query-key pair); the recomputing dQ kernel three (S, dP, dQ: 6*D), the dQ-from-dS kernel one (2*D)
         dkdv_flops = flops_bwd * 4.0 / 5.0
         main_tflops = dkdv_flops / (kernel_ms["attn_bwd_dkdv_kernel"] * 1e-3) / 1e12
-        dq_tflops = flops_bwd * 3.0 / 5.0 / (kernel_ms["attn_bwd_dq_kernel"] * 1e-3) / 1e12
+        dq_tflops = flops_bwd * (1.0 if spill else 3.0) / 5.0 / (kernel_ms[dq_name] * 1e-3) / 1e12
         out["bwd"] = {"ms": round(bwd_ms, 4), "tflops": round(bwd_tflops, 2),
                       "frac_of_mfma_peak": round(bwd_tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
         delta_bytes = 2 * B * H * N * D * 2 + B * H * N * 4       # read O, dO; write Delta
@@ -353,12 +371,18 @@ def main():
                               "algorithmic_GBps": round(delta_bytes / (kernel_ms["attn_bwd_delta_kernel"] * 1e-3) / 1e9, 1),
                               "hbm_peak_GBps": HBM_PEAK_GBS,
                               "frac_of_hbm_peak": round(delta_bytes / (kernel_ms["attn_bwd_delta_kernel"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        out["dq_kernel"] = {"ms": round(kernel_ms["attn_bwd_dq_kernel"], 4), "executed_tflops": round(dq_tflops, 2),
+        out["dq_kernel"] = {"name": dq_name, "ms": round(kernel_ms[dq_name], 4), "executed_tflops": round(dq_tflops, 2),
                             "frac_of_mfma_peak": round(dq_tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
+        if spill:
+            # kept pairs -> bytes of dS the dQ-from-dS kernel reads back (2 bytes per pair; diagonal blocks are read whole)
+            ds_read = flops_bwd / (10.0 * D) * 2.0
+            out["dq_kernel"]["algorithmic_ds_GBps"] = round(ds_read / (kernel_ms[dq_name] * 1e-3) / 1e9, 1)
+            out["dq_kernel"]["frac_of_hbm_peak"] = round(ds_read / (kernel_ms[dq_name] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
         out["roofline"] = {"kernel": "attn_bwd_dkdv_kernel", "bound": "mfma", "achieved": round(main_tflops, 2),
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": round(main_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                           **measured_traffic(w.name, "attn_bwd_dkdv_kernel"), "flops_per_launch": dkdv_flops}
+                           **measured_traffic(w.name + ("" if spill else "/recompute"), "attn_bwd_dkdv_kernel"),
+                           "flops_per_launch": dkdv_flops}
     else:
         out["roofline"] = {"kernel": "attn_fwd_kernel", "bound": "mfma", "achieved": round(fwd_tflops, 2),
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",

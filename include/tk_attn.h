@@ -86,7 +86,14 @@ int tk_attn_fwd(const void* q, const void* k, const void* v,
  *                   16-byte aligned; holds Delta (fp32 [B,H,N]).  It need not be cleared;
  *                   contents after the call are unspecified.  Two calls that overlap in time
  *                   must not share a workspace.
- * No atomics are used: dQ, dK and dV are bit-reproducible from run to run.
+ *                   The call runs in one of two forms, chosen by workspace_bytes alone:
+ *                   >= tk_attn_bwd_spill_workspace_bytes(B,H,N,N,D): the dK/dV kernel also stores
+ *                      its bf16 dS blocks (2 bytes per query-key pair of the padded problem) in the
+ *                      workspace and dQ = scale * dS K is formed from them: 10*D flops per pair;
+ *                   smaller: dS is recomputed by a dQ kernel of its own (14*D flops per pair).
+ *                   Both are the formulas above with the same roundings of P and dS; they differ
+ *                   in summation order only.
+ * No atomics are used: for a given form dQ, dK and dV are bit-reproducible from run to run.
  */
 int tk_attn_bwd(const void* q, const void* k, const void* v,
                 const void* o, const void* d_o, const float* lse,
@@ -97,6 +104,13 @@ int tk_attn_bwd(const void* q, const void* k, const void* v,
 
 /* Bytes of workspace tk_attn_bwd needs for this shape; 0 if the shape is invalid. */
 size_t tk_attn_bwd_workspace_bytes(int B, int H, int N, int D);
+
+/*
+ * Bytes of workspace from which tk_attn_bwd / _gqa / _rect take the faster form that stores dS:
+ * Delta plus one 2 KB block per (query head, 128-key tile, 32-query block, 32 keys), i.e. about
+ * 2 * B * Hq * Nq * Nk bytes (8.6 GB for B*Hq = 256, Nq = Nk = 4096).  0 if the shape is invalid.
+ */
+size_t tk_attn_bwd_spill_workspace_bytes(int B, int Hq, int Nq, int Nk, int D);
 
 /*
  * tk_attn_bwd for callers that cannot allocate device memory and have no workspace to hand over: code
@@ -186,6 +200,22 @@ int tk_attn_bwd_gqa(const void* q, const void* k, const void* v,
 int tk_attn_bwd_dq_delta(const void* q, const void* k, const void* v, const void* o, const void* d_o,
                          const float* lse, float* delta, void* dq,
                          int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream);
+
+/*
+ * The stages of the form of tk_attn_bwd that stores dS, after tk_attn_bwd_delta: dK/dV with the dS blocks
+ * written to ds (tk_attn_bwd_ds_bytes(B, Hq, N, N, D) bytes, 16-byte aligned, need not be cleared), then
+ * dQ = scale * dS K from those blocks (k: the same keys; the same B, Hq, Hkv, N, D, causal as the call
+ * that wrote ds).  The block layout is private to the two kernels.
+ */
+size_t tk_attn_bwd_ds_bytes(int B, int Hq, int Nq, int Nk, int D);
+
+int tk_attn_bwd_dkdv_ds(const void* q, const void* k, const void* v, const void* d_o,
+                        const float* lse, const float* delta,
+                        void* dk, void* dv, void* ds,
+                        int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream);
+
+int tk_attn_bwd_dq_from_ds(const void* k, const void* ds, void* dq,
+                           int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream);
 
 /* Stages 2 and 3 of the three-stage form (stage 1 is tk_attn_bwd_delta with H = Hq). */
 int tk_attn_bwd_dkdv_gqa(const void* q, const void* k, const void* v, const void* d_o,

@@ -25,7 +25,8 @@ TK_ERR_SCRATCH_LIMIT = -7
 EXPORTS = ("tk_attn_fwd", "tk_attn_bwd", "tk_attn_bwd_workspace_bytes", "tk_attn_bwd_delta",
            "tk_attn_bwd_dkdv", "tk_attn_bwd_dq", "tk_attn_fwd_gqa", "tk_attn_bwd_gqa", "tk_attn_bwd_dkdv_gqa",
            "tk_attn_bwd_dq_gqa", "tk_attn_bwd_dq_delta", "tk_attn_fwd_rect", "tk_attn_bwd_rect", "tk_attn_decode",
-           "tk_attn_decode_workspace_bytes", "tk_attn_decode_plan", "tk_attn_bwd_noalloc", "tk_attn_bwd_noalloc_max_rows", "tk_rotary", "tk_gemm", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
+           "tk_attn_decode_workspace_bytes", "tk_attn_decode_plan", "tk_attn_bwd_noalloc", "tk_attn_bwd_noalloc_max_rows",
+           "tk_attn_bwd_spill_workspace_bytes", "tk_attn_bwd_ds_bytes", "tk_attn_bwd_dkdv_ds", "tk_attn_bwd_dq_from_ds", "tk_rotary", "tk_gemm", "tk_mfma_probe", "tk_status_string", "tk_attn_version")
 
 _lib = None
 
@@ -55,6 +56,14 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.tk_attn_bwd_noalloc.restype = i
     lib.tk_attn_bwd_noalloc_max_rows.argtypes = []
     lib.tk_attn_bwd_noalloc_max_rows.restype = sz
+    lib.tk_attn_bwd_spill_workspace_bytes.argtypes = [i, i, i, i, i]
+    lib.tk_attn_bwd_spill_workspace_bytes.restype = sz
+    lib.tk_attn_bwd_ds_bytes.argtypes = [i, i, i, i, i]
+    lib.tk_attn_bwd_ds_bytes.restype = sz
+    lib.tk_attn_bwd_dkdv_ds.argtypes = [vp, vp, vp, vp, fp, fp, vp, vp, vp, i, i, i, i, i, i, f, vp]
+    lib.tk_attn_bwd_dkdv_ds.restype = i
+    lib.tk_attn_bwd_dq_from_ds.argtypes = [vp, vp, vp, i, i, i, i, i, i, f, vp]
+    lib.tk_attn_bwd_dq_from_ds.restype = i
     lib.tk_attn_bwd_workspace_bytes.argtypes = [i, i, i, i]
     lib.tk_attn_bwd_workspace_bytes.restype = sz
     lib.tk_attn_bwd_delta.argtypes = [vp, vp, fp, i, i, i, i, vp]
@@ -152,6 +161,25 @@ def tk_attn_bwd_noalloc_max_rows() -> int:
 
 def tk_attn_bwd_workspace_bytes(B, H, N, D) -> int:
     return int(load_library().tk_attn_bwd_workspace_bytes(B, H, N, D))
+
+
+def tk_attn_bwd_spill_workspace_bytes(B, Hq, Nq, Nk, D) -> int:
+    return int(load_library().tk_attn_bwd_spill_workspace_bytes(B, Hq, Nq, Nk, D))
+
+
+def tk_attn_bwd_ds_bytes(B, Hq, Nq, Nk, D) -> int:
+    return int(load_library().tk_attn_bwd_ds_bytes(B, Hq, Nq, Nk, D))
+
+
+def tk_attn_bwd_dkdv_ds(q, k, v, d_o, lse, delta, dk, dv, ds, B, Hq, Hkv, N, D, causal, scale, stream=None) -> int:
+    return load_library().tk_attn_bwd_dkdv_ds(_ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(lse), _ptr(delta),
+                                              _ptr(dk), _ptr(dv), _ptr(ds), B, Hq, Hkv, N, D, int(bool(causal)),
+                                              float(scale), _stream(stream))
+
+
+def tk_attn_bwd_dq_from_ds(k, ds, dq, B, Hq, Hkv, N, D, causal, scale, stream=None) -> int:
+    return load_library().tk_attn_bwd_dq_from_ds(_ptr(k), _ptr(ds), _ptr(dq), B, Hq, Hkv, N, D, int(bool(causal)),
+                                                 float(scale), _stream(stream))
 
 
 def tk_attn_bwd_delta(o, d_o, delta, B, H, N, D, stream=None) -> int:
@@ -258,11 +286,19 @@ def attn_fwd(q, k, v, causal: bool, scale: float, out=None, stream=None):
     return o, lse
 
 
-def alloc_bwd_workspace(B, H, N, D, device="cuda"):
-    nbytes = tk_attn_bwd_workspace_bytes(B, H, N, D)
-    if nbytes == 0:
+SPILL_WORKSPACE_LIMIT = 24 << 30     # largest dS workspace the convenience wrappers allocate by themselves
+
+
+def alloc_bwd_workspace(B, H, N, D, device="cuda", spill=None, Nk=None):
+    """Backward workspace.  spill=True: large enough for the form that stores dS (about 2*B*H*N*Nk bytes);
+    spill=False: Delta only; spill=None: the large one if it stays under SPILL_WORKSPACE_LIMIT."""
+    small = tk_attn_bwd_workspace_bytes(B, H, N, D)
+    if small == 0:
         raise TkAttnError(TK_ERR_BAD_DIM, "tk_attn_bwd_workspace_bytes")
-    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+    big = tk_attn_bwd_spill_workspace_bytes(B, H, N, N if Nk is None else Nk, D)
+    if spill is None:
+        spill = 0 < big <= SPILL_WORKSPACE_LIMIT
+    return torch.empty(big if spill else small, dtype=torch.uint8, device=device)
 
 
 def attn_bwd(q, k, v, o, d_o, lse, causal: bool, scale: float, workspace=None, out=None, stream=None):
@@ -358,7 +394,7 @@ def rect_bwd(q, k, v, o, d_o, lse, causal: bool, scale: float, workspace=None, s
     _check_bf16("d_o", d_o, q.shape)
     _check_f32("lse", lse, (B, Hq, Nq))
     if workspace is None:
-        workspace = alloc_bwd_workspace(B, Hq, Nq, D, q.device)
+        workspace = alloc_bwd_workspace(B, Hq, Nq, D, q.device, Nk=Nk)
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
     rc = tk_attn_bwd_rect(q, k, v, o, d_o, lse, dq, dk, dv, B, Hq, Hkv, Nq, Nk, D, causal, scale,
                           workspace, workspace.numel() * workspace.element_size(), stream)

@@ -18,6 +18,13 @@
 // for the whole chip), and a 128-key tile needs N/128 partial sums per dQ element, which made
 // the atomics alone as long as all the matrix work.  The split is also deterministic.
 //
+// With a large workspace (the chip has 288 GB) the recomputation goes away as well: kernel 2 then
+// also stores its bf16 dS blocks, 2 bytes per (query, key) pair, exactly as its lanes hold them
+// (SPILL), and dQ becomes one product per pair,
+//   kernel 4  dQ_i = scale * sum_j dS_ij K_j  from the stored blocks (attn_bwd_dq_from_ds_kernel),
+// which is bound by reading dS back from HBM instead of by 6*D flops per pair.  10*D flops per
+// pair are executed instead of 14*D; Delta then comes from kernel 1.
+//
 // In kernel 2, S and dP are produced with the KEY index on lanes and the query index on
 // registers, so P and dS in accumulator layout are directly the B operands of the two products
 // contracted over queries; their A operands (dO^T, Q^T) come from row-major LDS tiles via
@@ -112,12 +119,19 @@ template <int D> __device__ __forceinline__ int swz(int row) {
 // Nq queries, Nk keys.  TAIL: the general case (Nq != Nk, or a length that is not a multiple of
 // 128); the aligned square case compiles without any of the tail code.  Causal: query i sees keys
 // j <= i + (Nk - Nq), Nq <= Nk.
-template <int D, bool CAUSAL, bool TAIL>
+//
+// SPILL: every 32-key x 32-query block of dS is also written to DS as the wave holds it after the
+// conversion to bf16: 2 KB per block, [2 halves][64 lanes][16 bytes], where lane (key k = lane % 32,
+// h = lane / 32) holds in half s the queries 16s + 8g + 4h + t (g = 0..1, t = 0..3) of the block, at
+// element 4g + t.  Block (query head, key tile kt, query block qb, wave w) sits at
+// (((head * num_kv_tiles + kt) * n_qb + qb) * 4 + w) * 2048 bytes.  Masked pairs and padding rows hold 0.
+template <int D, bool CAUSAL, bool TAIL, bool SPILL>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1)
 void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K, const bf16* __restrict__ V,
                           const bf16* __restrict__ dO, const float* __restrict__ LSE, const float* __restrict__ Delta,
                           bf16* __restrict__ dK, bf16* __restrict__ dV,
-                          int Nq, int Nk, int num_kv_tiles, int total_units, float scale, int hq, int hkv)
+                          int Nq, int Nk, int num_kv_tiles, int total_units, float scale, int hq, int hkv,
+                          char* __restrict__ DS, int n_qb)
 {
     using S = DkdvShape<D>;
     __shared__ __attribute__((aligned(1024))) char ring[S::kStages * S::kStageBytes];
@@ -362,7 +376,7 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     // One query block.  cur receives this block's transposed fragments and bf16 P / dS; prev holds
     // those of the previous block, whose dV^T / dK^T products run here, interleaved with this block's
     // vector-ALU work (P, dS), so that the matrix pipe has work while the ALU is busy.
-    auto step = [&](auto masked, int blk, Late& cur, const Late& prev) {
+    auto step = [&](auto masked, int blk, Late& cur, const Late& prev, char* ds_head) {
         const int i0 = i_begin + blk * S::kTileQ;
         const char* qs = ring + ((c_count + blk) & (S::kStages - 1)) * S::kStageBytes;
         const char* qs_next = ring + ((c_count + blk + 1) & (S::kStages - 1)) * S::kStageBytes;
@@ -396,6 +410,11 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
             for (int r = 0; r < 16; r++)
                 if (i0 + 8 * (r >> 2) + 4 * h + (r & 3) + off < my_j) s[r] = -INFINITY;
         }
+        // a padding key (row >= Nk) was computed from the last real row: its dS must not reach dQ
+        if (TAIL && SPILL && my_j >= Nk) {
+#pragma unroll
+            for (int r = 0; r < 16; r++) s[r] = -INFINITY;
+        }
 #pragma unroll
         for (int g = 0; g < 4; g++) {
 #pragma unroll
@@ -411,6 +430,11 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
             const int r0 = 8 * ks;
             cur.pb[ks] = cvt8(s[r0], s[r0 + 1], s[r0 + 2], s[r0 + 3], s[r0 + 4], s[r0 + 5], s[r0 + 6], s[r0 + 7]);
             cur.dsb[ks] = cvt8(dp[r0], dp[r0 + 1], dp[r0 + 2], dp[r0 + 3], dp[r0 + 4], dp[r0 + 5], dp[r0 + 6], dp[r0 + 7]);
+        }
+        if (SPILL) {
+            char* blk_ptr = ds_head + ((size_t)(i0 / S::kTileQ) * 4 + wave) * 2048;     // wave-uniform
+            *(bf16x8*)(blk_ptr + lane * 16) = cur.dsb[0];
+            *(bf16x8*)(blk_ptr + 1024 + lane * 16) = cur.dsb[1];
         }
 #pragma unroll
         for (int idx = 0; idx < kSteps; idx++) {
@@ -429,8 +453,11 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         // next iteration reads its rows; the newer prefetches may stay in flight (wave 0 issues one
         // more load per block).  The wave's own LDS reads of this block's stage must have returned as
         // well: after the barrier the next step's prefetch overwrites that stage.
-        if (wave == 0) wait_vmcnt_lds_done<(S::kAhead - 2) * (S::kLoadsPerBlock + 1)>();
-        else wait_vmcnt_lds_done<(S::kAhead - 2) * S::kLoadsPerBlock>();
+        // (the counter retires loads and stores in issue order: the two dS stores of this step and of the
+        // previous one are younger than the loads waited for)
+        constexpr int kStores = SPILL ? 4 : 0;
+        if (wave == 0) wait_vmcnt_lds_done<(S::kAhead - 2) * (S::kLoadsPerBlock + 1) + kStores>();
+        else wait_vmcnt_lds_done<(S::kAhead - 2) * S::kLoadsPerBlock + kStores>();
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
@@ -440,27 +467,33 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     // the ones that may touch the diagonal.  The deferred products run on across the heads of the group.
 #pragma unroll 1
     for (int g = 0; g < group; g++) {
+        // dS blocks of (this query head, this key tile); query block 0 = queries 0..31 of the head
+        char* ds_head = nullptr;
+        if (SPILL) {
+            const size_t q_head = (size_t)(bh / hkv) * hq + (size_t)(bh % hkv) * group + g;
+            ds_head = DS + ((q_head * num_kv_tiles + kt) * n_qb) * (size_t)8192;
+        }
         int blk = 0;
         if (CAUSAL) {
 #pragma unroll 1
             for (; blk < n_masked; blk += 2) {
                 if (kDeferred) {
-                    step(std::true_type{}, blk, set_a, set_b);
-                    step(std::true_type{}, blk + 1, set_b, set_a);
+                    step(std::true_type{}, blk, set_a, set_b, ds_head);
+                    step(std::true_type{}, blk + 1, set_b, set_a, ds_head);
                 } else {
-                    step(std::true_type{}, blk, set_a, set_a);
-                    step(std::true_type{}, blk + 1, set_a, set_a);
+                    step(std::true_type{}, blk, set_a, set_a, ds_head);
+                    step(std::true_type{}, blk + 1, set_a, set_a, ds_head);
                 }
             }
         }
 #pragma unroll 1
         for (; blk < n_blocks; blk += 2) {
             if (kDeferred) {
-                step(std::false_type{}, blk, set_a, set_b);
-                step(std::false_type{}, blk + 1, set_b, set_a);
+                step(std::false_type{}, blk, set_a, set_b, ds_head);
+                step(std::false_type{}, blk + 1, set_b, set_a, ds_head);
             } else {
-                step(std::false_type{}, blk, set_a, set_a);
-                step(std::false_type{}, blk + 1, set_a, set_a);
+                step(std::false_type{}, blk, set_a, set_a, ds_head);
+                step(std::false_type{}, blk + 1, set_a, set_a, ds_head);
             }
         }
         c_count += n_blocks;
@@ -511,10 +544,10 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     wait_vmcnt<0>();      // the spare prefetches of the last blocks must not outlive the workgroup's LDS
 }
 
-template <int D, bool CAUSAL, bool TAIL>
+template <int D, bool CAUSAL, bool TAIL, bool SPILL>
 static hipError_t launch_dkdv_tt(const void* q, const void* k, const void* v, const void* d_o,
                                  const float* lse, const float* delta, void* dk, void* dv,
-                                 int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
+                                 int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream, void* ds)
 {
     using S = DkdvShape<D>;
     const int num_kv_tiles = (Nk + S::kTileKV - 1) / S::kTileKV;
@@ -524,31 +557,36 @@ static hipError_t launch_dkdv_tt(const void* q, const void* k, const void* v, co
     if (e != hipSuccess) return e;
     const int resident = cus * (D == 64 ? 2 : 1);               // as many workgroups as fit at once
     const int grid = total_units < resident ? total_units : resident;
-    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL, TAIL>), dim3(grid), dim3(S::kThreads), 0, stream,
+    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL, TAIL, SPILL>), dim3(grid), dim3(S::kThreads), 0, stream,
                        (const bf16*)q, (const bf16*)k, (const bf16*)v, (const bf16*)d_o, lse, delta,
-                       (bf16*)dk, (bf16*)dv, Nq, Nk, num_kv_tiles, total_units, scale, H, Hkv);
+                       (bf16*)dk, (bf16*)dv, Nq, Nk, num_kv_tiles, total_units, scale, H, Hkv,
+                       (char*)ds, ds_query_blocks(Nq));
     return hipGetLastError();
 }
 
 template <int D, bool CAUSAL>
 static hipError_t launch_dkdv_t(const void* q, const void* k, const void* v, const void* d_o,
                                 const float* lse, const float* delta, void* dk, void* dv,
-                                int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
+                                int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream, void* ds)
 {
     using S = DkdvShape<D>;
-    return (Nq != Nk || Nk % S::kTileKV)
-               ? launch_dkdv_tt<D, CAUSAL, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream)
-               : launch_dkdv_tt<D, CAUSAL, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream);
+    const bool tail = Nq != Nk || Nk % S::kTileKV;
+    if (ds) return tail ? launch_dkdv_tt<D, CAUSAL, true, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream, ds)
+                        : launch_dkdv_tt<D, CAUSAL, false, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream, ds);
+    return tail ? launch_dkdv_tt<D, CAUSAL, true, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream, ds)
+                : launch_dkdv_tt<D, CAUSAL, false, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream, ds);
 }
 
+// ds != nullptr: the kernel also stores its dS blocks there (ds_spill_bytes(...) bytes) for launch_attn_bwd_dq_from_ds
 hipError_t launch_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
                                 const float* lse, const float* delta, void* dk, void* dv,
-                                int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream)
+                                int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream,
+                                void* ds)
 {
-    if (D == 128) return causal ? launch_dkdv_t<128, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream)
-                                : launch_dkdv_t<128, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream);
-    return causal ? launch_dkdv_t<64, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream)
-                  : launch_dkdv_t<64, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream);
+    if (D == 128) return causal ? launch_dkdv_t<128, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream, ds)
+                                : launch_dkdv_t<128, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream, ds);
+    return causal ? launch_dkdv_t<64, true>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream, ds)
+                  : launch_dkdv_t<64, false>(q, k, v, d_o, lse, delta, dk, dv, B, H, Hkv, Nq, Nk, scale, stream, ds);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -810,6 +848,216 @@ hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const
                                 : launch_dq_t<128, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream, o, delta_out);
     return causal ? launch_dq_t<64, true>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream, o, delta_out)
                   : launch_dq_t<64, false>(q, k, v, d_o, lse, delta, dq, B, H, Hkv, Nq, Nk, scale, stream, o, delta_out);
+}
+
+// ------------------------------------------------------------------------------------------
+// kernel 4: dQ from the dS blocks that kernel 2 stored
+// ------------------------------------------------------------------------------------------
+template <int D>
+struct DqDsShape {
+    static constexpr int kWaves = 4;
+    static constexpr int kThreads = 256;
+    static constexpr int kTileQ = 128;                  // queries per workgroup (32 per wave)
+    static constexpr int kTileKV = 64;                  // keys per LDS stage
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kChunksPerRow = D / 8;
+    static constexpr int kKTileBytes = kTileKV * kRowBytes;
+    static constexpr int kDsWaveBytes = 2 * 2048;       // two 32-key blocks of this wave's 32 queries
+    static constexpr int kStageBytes = kKTileBytes + kWaves * kDsWaveBytes;
+    static constexpr int kKLoads = kTileKV * kChunksPerRow / kThreads;   // per thread
+    static constexpr int kDsLoads = kDsWaveBytes / 1024;                  // per lane
+};
+
+// dQ_i = scale * sum_j dS_ij K_j: one workgroup per 128-query tile (causal: balanced pairs of tiles), wave w
+// owns queries 32w..32w+31 and keeps dQ^T in registers while it walks 64-key tiles.  dQ^T += K^T dS^T needs
+// dS^T with the QUERY on lanes, and the stored blocks have the KEY on lanes: each wave pulls its own blocks
+// into LDS with direct loads and takes the operand out with transposing reads.  The 16-byte pieces of a
+// block are placed at (key * 4 + half * 2 + h) * 16 so that a transposing read (4 keys x 4 query quads per
+// 16 lanes) touches every bank once.  No mask code: kernel 2 stored zeros for masked pairs, padding
+// queries and padding keys, and a wave skips the tiles that lie wholly beyond its diagonal (which kernel 2
+// may not have written).
+template <int D, bool CAUSAL, bool TAIL>
+__global__ __launch_bounds__(256, 2)
+void attn_bwd_dq_from_ds_kernel(const bf16* __restrict__ K, const char* __restrict__ DS, bf16* __restrict__ dQ,
+                                int Nq, int Nk, int num_q_tiles, int total_wg, float scale, int hq, int hkv,
+                                int num_kv_tiles, int n_qb)
+{
+    using S = DqDsShape<D>;
+    __shared__ __attribute__((aligned(1024))) char stage0[S::kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char stage1[S::kStageBytes];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int l32 = lane & 31;
+    const int h = lane >> 5;
+
+    const int units = CAUSAL ? (num_q_tiles + 1) / 2 : num_q_tiles;
+    const int logical = xcd_remap(blockIdx.x, total_wg);
+    const int bh = logical / units;                  // query head
+    const int unit = logical % units;
+    const size_t head = (size_t)bh * Nq * D;
+    const size_t kv_head = (size_t)((bh / hq) * hkv + (bh % hq) / (hq / hkv)) * Nk * D;
+    const int off = TAIL ? Nk - Nq : 0;              // causal: query i sees keys <= i + off
+    const bf16* Kh = K + kv_head;
+    const char* DSh = DS + (size_t)bh * num_kv_tiles * n_qb * 8192;
+
+    // K tile loads: slot arithmetic of the other kernels
+    int k_src[S::kKLoads];
+#pragma unroll
+    for (int it = 0; it < S::kKLoads; it++) {
+        int s = it * S::kThreads + tid;
+        int row = s / S::kChunksPerRow, pc = s % S::kChunksPerRow;
+        k_src[it] = row * D + ((pc ^ swz<D>(row)) * 8);
+    }
+    // dS block loads: LDS piece P = 64 * n + lane of a block holds (key P / 4, half (P / 2) % 2, h P % 2)
+    int ds_src[2];
+#pragma unroll
+    for (int n = 0; n < 2; n++) {
+        const int P = 64 * n + lane;
+        ds_src[n] = ((P >> 1) & 1) * 1024 + ((P & 1) * 32 + (P >> 2)) * 16;
+    }
+
+    // transposed operand from the K tile (A of dQ^T = K^T dS^T): rows 16*kk + 4h + j16/4 (+8)
+    const int j16 = lane & 15;
+    const int tr_row = 4 * h + (j16 >> 2);
+    const int tr_lane = tr_row * S::kRowBytes + (((2 * ((lane >> 4) & 1) + ((j16 & 3) >> 1)) ^ swz<D>(tr_row)) << 4) + ((j16 & 1) << 3);
+    // dS^T operand (B): 16-lane group G = lane / 16 covers queries 16 * (G % 2) .. + 15 (= half G % 2 of the
+    // block) and keys 4 * (G / 2) + j16 / 4 (+ 8) of a 16-key step; lane j of the group points at the query
+    // quad j % 4, i.e. (h = quad % 2, g = quad / 2) of the stored layout
+    const int ds_lane = (4 * h + (j16 >> 2)) * 64 + ((lane >> 4) & 1) * 32 + (j16 & 1) * 16 + ((j16 & 3) >> 1) * 8;
+
+#pragma unroll 1
+    for (int pass = 0; pass < (CAUSAL ? 2 : 1); pass++) {
+    const int qt = pass == 0 ? num_q_tiles - 1 - unit : unit;
+    if (pass == 1 && qt == num_q_tiles - 1 - unit) break;   // odd tile count: the middle tile has no partner
+    const int q0 = qt * S::kTileQ + wave * 32;
+    const int my_q = q0 + l32;
+    const int qb = qt * 4 + wave;                    // this wave's query block
+
+    auto issue_tile = [&](char* base, int tile) {
+        const int j0 = tile * S::kTileKV;
+        const bf16* kt = Kh + (size_t)j0 * D;
+        if (!TAIL || j0 + S::kTileKV <= Nk) {
+#pragma unroll
+            for (int it = 0; it < S::kKLoads; it++)
+                load_global_to_lds16(kt + k_src[it], base + wave * 1024 + it * (S::kThreads * 16));
+        } else {
+#pragma unroll
+            for (int it = 0; it < S::kKLoads; it++) {
+                const int row = j0 + (it * S::kThreads + tid) / S::kChunksPerRow;
+                const int back = (row < Nk ? 0 : row - (Nk - 1)) * D;   // rows >= Nk fetch row Nk-1 (their dS is 0)
+                load_global_to_lds16(kt + k_src[it] - back, base + wave * 1024 + it * (S::kThreads * 16));
+            }
+        }
+        // the two 32-key blocks (waves 2*(tile%2), +1 of kernel 2) of key tile tile/2 for this wave's query block;
+        // a wave whose diagonal lies before this tile skips it: nothing may have been stored there
+        if (!(CAUSAL && j0 > q0 + 31 + off) && !(TAIL && q0 >= Nq)) {
+            const char* blk = DSh + (((size_t)(tile >> 1) * n_qb + qb) * 4 + 2 * (tile & 1)) * 2048;
+            char* dst = base + S::kKTileBytes + wave * S::kDsWaveBytes;
+#pragma unroll
+            for (int c = 0; c < 2; c++)
+#pragma unroll
+                for (int n = 0; n < 2; n++)
+                    load_global_to_lds16(blk + c * 2048 + ds_src[n], dst + c * 2048 + n * 1024);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    f32x16 dq_acc[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; db++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) dq_acc[db][r] = 0.f;
+
+    auto compute_tile = [&](const char* ks, int tile) {
+        const int j0 = tile * S::kTileKV;
+        if (CAUSAL && j0 > q0 + 31 + off) return;    // every key of the tile is masked for this wave
+        if (TAIL && q0 >= Nq) return;                // a wave of padding rows only
+        const char* dss = ks + S::kKTileBytes + wave * S::kDsWaveBytes;
+#pragma unroll
+        for (int kk = 0; kk < 4; kk++) {             // 16 keys per step
+            const int ds_off = (kk >> 1) * 2048 + (kk & 1) * 1024;
+            bf16x4 b0 = lds_read_tr16(dss, ds_lane + ds_off);
+            bf16x4 b1 = lds_read_tr16(dss, ds_lane + ds_off + 512);
+            const bf16x8 dsb = concat(b0, b1);
+#pragma unroll
+            for (int db = 0; db < D / 32; db++) {
+                const int row_off = 16 * kk * S::kRowBytes;
+                const int x0 = (4 * db) << 4, x1 = ((4 * db) ^ 2) << 4;
+                bf16x4 a0 = lds_read_tr16(ks, (tr_lane ^ x0) + row_off);
+                bf16x4 a1 = lds_read_tr16(ks, (tr_lane ^ x1) + row_off + 8 * S::kRowBytes);
+                dq_acc[db] = mfma32(concat(a0, a1), dsb, dq_acc[db]);
+            }
+        }
+    };
+
+    int n_tiles;
+    if (!TAIL) {
+        n_tiles = (CAUSAL ? qt * S::kTileQ + S::kTileQ : num_q_tiles * S::kTileQ) / S::kTileKV;
+    } else {
+        int n_keys = Nk;
+        if (CAUSAL && qt * S::kTileQ + S::kTileQ + off < n_keys) n_keys = qt * S::kTileQ + S::kTileQ + off;
+        n_tiles = 2 * ((n_keys + 2 * S::kTileKV - 1) / (2 * S::kTileKV));
+    }
+    issue_tile(stage0, 0);
+    wait_vmcnt<0>();
+    __syncthreads();
+    for (int t = 0; t < n_tiles; t += 2) {
+        issue_tile(stage1, t + 1);
+        compute_tile(stage0, t);
+        wait_vmcnt<0>();
+        __syncthreads();
+        if (t + 2 < n_tiles) issue_tile(stage0, t + 2);
+        compute_tile(stage1, t + 1);
+        wait_vmcnt<0>();
+        __syncthreads();
+    }
+
+    if (!TAIL || my_q < Nq) {
+        bf16* dQr = dQ + head + (size_t)my_q * D;
+#pragma unroll
+        for (int db = 0; db < D / 32; db++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                bf16x2 lo = cvt2(dq_acc[db][4 * g + 0] * scale, dq_acc[db][4 * g + 1] * scale);
+                bf16x2 hi = cvt2(dq_acc[db][4 * g + 2] * scale, dq_acc[db][4 * g + 3] * scale);
+                *(bf16x4*)(dQr + 32 * db + 8 * g + 4 * h) = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+            }
+    }
+    }   // pass
+}
+
+template <int D, bool CAUSAL, bool TAIL>
+static hipError_t launch_dq_from_ds_tt(const void* k, const void* ds, void* dq,
+                                       int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
+{
+    using S = DqDsShape<D>;
+    const int num_q_tiles = (Nq + S::kTileQ - 1) / S::kTileQ;
+    const int num_kv_tiles = (Nk + 127) / 128;
+    const int total = B * H * (CAUSAL ? (num_q_tiles + 1) / 2 : num_q_tiles);
+    hipLaunchKernelGGL((attn_bwd_dq_from_ds_kernel<D, CAUSAL, TAIL>), dim3(total), dim3(S::kThreads), 0, stream,
+                       (const bf16*)k, (const char*)ds, (bf16*)dq, Nq, Nk, num_q_tiles, total, scale, H, Hkv,
+                       num_kv_tiles, ds_query_blocks(Nq));
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_dq_from_ds_t(const void* k, const void* ds, void* dq,
+                                      int B, int H, int Hkv, int Nq, int Nk, int causal, float scale, hipStream_t stream)
+{
+    const bool tail = Nq != Nk || Nq % 128;
+    if (causal) return tail ? launch_dq_from_ds_tt<D, true, true>(k, ds, dq, B, H, Hkv, Nq, Nk, scale, stream)
+                            : launch_dq_from_ds_tt<D, true, false>(k, ds, dq, B, H, Hkv, Nq, Nk, scale, stream);
+    return tail ? launch_dq_from_ds_tt<D, false, true>(k, ds, dq, B, H, Hkv, Nq, Nk, scale, stream)
+                : launch_dq_from_ds_tt<D, false, false>(k, ds, dq, B, H, Hkv, Nq, Nk, scale, stream);
+}
+
+hipError_t launch_attn_bwd_dq_from_ds(const void* k, const void* ds, void* dq,
+                                      int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream)
+{
+    return D == 128 ? launch_dq_from_ds_t<128>(k, ds, dq, B, H, Hkv, Nq, Nk, causal, scale, stream)
+                    : launch_dq_from_ds_t<64>(k, ds, dq, B, H, Hkv, Nq, Nk, causal, scale, stream);
 }
 
 }  // namespace tk

@@ -204,6 +204,44 @@ size_t tk_attn_bwd_workspace_bytes(int B, int H, int N, int D)
     return delta_bytes(B, H, N);
 }
 
+size_t tk_attn_bwd_spill_workspace_bytes(int B, int Hq, int Nq, int Nk, int D)
+{
+    if (check_lengths(B, Hq, Hq, Nq, Nk, D, 0) != TK_OK) return 0;
+    return delta_bytes(B, Hq, Nq) + tk::ds_spill_bytes(B, Hq, Nq, Nk);
+}
+
+size_t tk_attn_bwd_ds_bytes(int B, int Hq, int Nq, int Nk, int D)
+{
+    if (check_lengths(B, Hq, Hq, Nq, Nk, D, 0) != TK_OK) return 0;
+    return tk::ds_spill_bytes(B, Hq, Nq, Nk);
+}
+
+int tk_attn_bwd_dkdv_ds(const void* q, const void* k, const void* v, const void* d_o,
+                        const float* lse, const float* delta, void* dk, void* dv, void* ds,
+                        int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream)
+{
+    if (!q || !k || !v || !d_o || !lse || !delta || !dk || !dv || !ds) return TK_ERR_NULL_PTR;
+    if (int rc = check_lengths(B, Hq, Hkv, N, N, D, causal)) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(lse) ||
+        !aligned16(delta) || !aligned16(dk) || !aligned16(dv) || !aligned16(ds))
+        return TK_ERR_MISALIGNED;
+    if (int rc = check_scale(scale)) return rc;
+    hipError_t e = tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, N, N, D, causal != 0, scale,
+                                            (hipStream_t)stream, ds);
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
+int tk_attn_bwd_dq_from_ds(const void* k, const void* ds, void* dq,
+                           int B, int Hq, int Hkv, int N, int D, int causal, float scale, void* stream)
+{
+    if (!k || !ds || !dq) return TK_ERR_NULL_PTR;
+    if (int rc = check_lengths(B, Hq, Hkv, N, N, D, causal)) return rc;
+    if (!aligned16(k) || !aligned16(ds) || !aligned16(dq)) return TK_ERR_MISALIGNED;
+    if (int rc = check_scale(scale)) return rc;
+    hipError_t e = tk::launch_attn_bwd_dq_from_ds(k, ds, dq, B, Hq, Hkv, N, N, D, causal != 0, scale, (hipStream_t)stream);
+    return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;
+}
+
 int tk_attn_bwd_delta(const void* o, const void* d_o, float* delta, int B, int H, int N, int D, void* stream)
 {
     if (!o || !d_o || !delta) return TK_ERR_NULL_PTR;
@@ -290,6 +328,18 @@ int tk_attn_bwd_rect(const void* q, const void* k, const void* v, const void* o,
 
     hipStream_t s = (hipStream_t)stream;
     float* delta = (float*)workspace;
+    if (workspace_bytes >= tk_attn_bwd_spill_workspace_bytes(B, Hq, Nq, Nk, D)) {
+        // Large workspace: 10*D flops per (query, key) pair instead of 14*D.  Delta on its own, then dK/dV,
+        // which also leaves its bf16 dS blocks behind Delta in the workspace, then dQ = scale * dS K from them.
+        void* ds = (char*)workspace + delta_bytes(B, Hq, Nq);
+        if (tk::launch_attn_bwd_delta(o, d_o, delta, B, Hq, Nq, D, s) != hipSuccess) return TK_ERR_LAUNCH;
+        if (tk::launch_attn_bwd_dkdv(q, k, v, d_o, lse, delta, dk, dv, B, Hq, Hkv, Nq, Nk, D, causal != 0, scale, s, ds) != hipSuccess)
+            return TK_ERR_LAUNCH;
+        if (tk::launch_attn_bwd_dq_from_ds(k, ds, dq, B, Hq, Hkv, Nq, Nk, D, causal != 0, scale, s) != hipSuccess)
+            return TK_ERR_LAUNCH;
+        return TK_OK;
+    }
+    // Small workspace (Delta only): dS is recomputed by a dQ kernel of its own.
     // 1. dQ per query tile; the kernel also forms Delta = rowsum(dO * O) for its rows (each lane holds its
     //    query's dO row anyway) and leaves it in the workspace, which saves a pass over O and dO
     if (tk::launch_attn_bwd_dq(q, k, v, d_o, lse, nullptr, dq, B, Hq, Hkv, Nq, Nk, D, causal != 0, scale, s, o, delta) != hipSuccess)

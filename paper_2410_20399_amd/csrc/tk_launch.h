@@ -42,10 +42,23 @@ hipError_t launch_attn_fwd_splitk(const void* q, const void* k, const void* v, v
 hipError_t launch_attn_bwd_delta(const void* o, const void* d_o, float* delta,
                                  int B, int H, int N, int D, hipStream_t stream);
 
-// dK, dV (key-tile parallel)
+// The dS blocks that the dK/dV kernel can leave behind for launch_attn_bwd_dq_from_ds: one 2 KB block per
+// (query head, 128-key tile, 32-query block, wave of 32 keys).  Query blocks per head: the dK/dV kernel walks
+// them in pairs from a multiple of 32, so up to two past the last real one.
+inline int ds_query_blocks(int Nq) { return Nq / 32 + 2; }
+inline size_t ds_spill_bytes(int B, int H, int Nq, int Nk) {
+    return (size_t)B * H * (size_t)((Nk + 127) / 128) * (size_t)ds_query_blocks(Nq) * 8192;
+}
+
+// dK, dV (key-tile parallel).  ds != nullptr: also store the dS blocks there (ds_spill_bytes(B, H, Nq, Nk) bytes).
 hipError_t launch_attn_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o,
                                 const float* lse, const float* delta, void* dk, void* dv,
-                                int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream);
+                                int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream,
+                                void* ds = nullptr);
+
+// dQ = scale * dS K from the blocks a launch_attn_bwd_dkdv call with the same shape arguments stored
+hipError_t launch_attn_bwd_dq_from_ds(const void* k, const void* ds, void* dq,
+                                      int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream);
 
 // dQ (query-tile parallel).  With o != nullptr the kernel computes Delta itself from o and d_o, writes it to
 // delta_out (for the dK/dV kernel launched after it) and does not read delta.

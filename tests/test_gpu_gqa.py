@@ -49,14 +49,16 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("spill", [False, True], ids=["recompute", "spill"])
 @pytest.mark.parametrize("B,Hq,Hkv,N,D,causal", CASES)
-def test_gqa_forward_backward(attn, B, Hq, Hkv, N, D, causal):
+def test_gqa_forward_backward(attn, B, Hq, Hkv, N, D, causal, spill):
     q, k, v, d_o = make(20657 + Hq * 7 + N + D, B, Hq, Hkv, N, D)
     scale = 1 / math.sqrt(D)
     print(f"launch gqa fwd/bwd B{B} Hq{Hq} Hkv{Hkv} N{N} D{D} causal={causal}", flush=True)
     qd, kd, vd, dod = (t.cuda() for t in (q, k, v, d_o))
     o, lse = attn.gqa_fwd(qd, kd, vd, causal, scale)
-    dq, dk, dv = attn.gqa_bwd(qd, kd, vd, o, dod, lse, causal, scale)
+    ws = attn.alloc_bwd_workspace(B, Hq, N, D, spill=spill)     # (spill: the form of the backward that stores dS)
+    dq, dk, dv = attn.gqa_bwd(qd, kd, vd, o, dod, lse, causal, scale, workspace=ws)
     torch.cuda.synchronize()
     o_ref, lse_ref = orc.gqa_fwd(f64(q), f64(k), f64(v), causal, scale)
     eo = np.abs(f64(o.cpu()) - o_ref)

@@ -59,14 +59,19 @@ SMALL = [
 ]
 
 
+@pytest.mark.parametrize("spill", [False, True], ids=["recompute", "spill"])
 @pytest.mark.parametrize("B,H,N,D,causal", SMALL)
-def test_small_forward_backward(attn, B, H, N, D, causal):
+def test_small_forward_backward(attn, B, H, N, D, causal, spill):
+    """spill: which form of the backward runs - dS recomputed by the dQ kernel (workspace = Delta only), or dS
+    stored by the dK/dV kernel and dQ formed from it (large workspace)."""
     q, k, v, d_o = workloads.make_small(20600 + N + D, B, H, N, D)
     scale = 1 / math.sqrt(D)
-    print(f"launch fwd/bwd B{B} H{H} N{N} D{D} causal={causal}", flush=True)
+    print(f"launch fwd/bwd B{B} H{H} N{N} D{D} causal={causal} spill={spill}", flush=True)
     qd, kd, vd, dod = (t.cuda() for t in (q, k, v, d_o))
     o, lse = attn.attn_fwd(qd, kd, vd, causal, scale)
-    dq, dk, dv = attn.attn_bwd(qd, kd, vd, o, dod, lse, causal, scale)
+    ws = attn.alloc_bwd_workspace(B, H, N, D, spill=spill)
+    ws.fill_(0xFF)
+    dq, dk, dv = attn.attn_bwd(qd, kd, vd, o, dod, lse, causal, scale, workspace=ws)
     torch.cuda.synchronize()
     o_ref, lse_ref = orc.attn_fwd(f64(q), f64(k), f64(v), causal, scale)
     check_forward(o, lse, o_ref, lse_ref, (B, H, N, D, causal))
@@ -122,8 +127,8 @@ def test_full_size_forward_sampled_rows(attn, idx):
         assert torch.equal(o[:, :, 0], v[:, :, 0])
 
 
-@pytest.mark.parametrize("idx,n_heads", [(4, 3), (5, 1), (6, 2), (7, 2)])
-def test_full_size_backward_sampled_heads(attn, idx, n_heads):
+@pytest.mark.parametrize("idx,n_heads,spill", [(4, 3, True), (4, 1, False), (5, 1, True), (5, 1, False), (6, 2, True), (6, 1, False), (7, 2, True)])
+def test_full_size_backward_sampled_heads(attn, idx, n_heads, spill):
     """Full benchmark shape on the GPU (the launch configuration bench.py times); the oracle
     recomputes whole heads, which are independent problems."""
     w = workloads.WORKLOADS[idx]
@@ -131,8 +136,10 @@ def test_full_size_backward_sampled_heads(attn, idx, n_heads):
     print(f"launch fwd+bwd {w.name}", flush=True)
     qd, kd, vd, dod = (t.cuda() for t in (q, k, v, d_o))
     o, lse = attn.attn_fwd(qd, kd, vd, w.causal, w.scale)
-    dq, dk, dv = attn.attn_bwd(qd, kd, vd, o, dod, lse, w.causal, w.scale)
+    ws = attn.alloc_bwd_workspace(w.B, w.H, w.N, w.D, spill=spill)
+    dq, dk, dv = attn.attn_bwd(qd, kd, vd, o, dod, lse, w.causal, w.scale, workspace=ws)
     torch.cuda.synchronize()
+    del ws
     dq, dk, dv = dq.cpu(), dk.cpu(), dv.cpu()
     for t in (dq, dk, dv):
         assert torch.isfinite(t.float()).all()
@@ -143,8 +150,8 @@ def test_full_size_backward_sampled_heads(attn, idx, n_heads):
             check_grad(f64(g[b, h]), r, (w.name, name, b, h))
 
 
-@pytest.mark.parametrize("idx", [4, 5, 6])
-def test_full_size_every_head_equals_the_head_run_alone(attn, idx):
+@pytest.mark.parametrize("idx,spill", [(4, True), (5, True), (6, True), (6, False)])
+def test_full_size_every_head_equals_the_head_run_alone(attn, idx, spill):
     """Completeness at full size.  Every kernel computes a head in an order that does not depend on
     where the head sits in the launch, so O, LSE, dQ, dK, dV of head (b, h) of the batched call must be
     bit-identical to a B = 1, H = 1 call on that head alone.  With the oracle check of the sampled heads
@@ -154,9 +161,11 @@ def test_full_size_every_head_equals_the_head_run_alone(attn, idx):
     print(f"launch fwd+bwd {w.name} batched", flush=True)
     qd, kd, vd, dod = (t.cuda() for t in (q, k, v, d_o))
     o, lse = attn.attn_fwd(qd, kd, vd, w.causal, w.scale)
-    dq, dk, dv = attn.attn_bwd(qd, kd, vd, o, dod, lse, w.causal, w.scale)
+    ws = attn.alloc_bwd_workspace(w.B, w.H, w.N, w.D, spill=spill)
+    dq, dk, dv = attn.attn_bwd(qd, kd, vd, o, dod, lse, w.causal, w.scale, workspace=ws)
     torch.cuda.synchronize()
-    ws1 = attn.alloc_bwd_workspace(1, 1, w.N, w.D)
+    del ws
+    ws1 = attn.alloc_bwd_workspace(1, 1, w.N, w.D, spill=spill)
     print(f"launch {w.B * w.H} single-head calls", flush=True)
     bad = []
     for b in range(w.B):

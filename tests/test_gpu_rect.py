@@ -54,8 +54,9 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("spill", [False, True], ids=["recompute", "spill"])
 @pytest.mark.parametrize("B,Hq,Hkv,Nq,Nk,D,causal", CASES)
-def test_rect_forward_backward(attn, B, Hq, Hkv, Nq, Nk, D, causal):
+def test_rect_forward_backward(attn, B, Hq, Hkv, Nq, Nk, D, causal, spill):
     g = torch.Generator().manual_seed(115200 + Nq * 7 + Nk * 3 + D + Hq)
     q = torch.randn(B, Hq, Nq, D, generator=g).to(torch.bfloat16)
     k = torch.randn(B, Hkv, Nk, D, generator=g).to(torch.bfloat16)
@@ -69,7 +70,8 @@ def test_rect_forward_backward(attn, B, Hq, Hkv, Nq, Nk, D, causal):
     dqbuf, dq = guarded((B, Hq, Nq, D), torch.bfloat16, 77.0)
     dkbuf, dk = guarded((B, Hkv, Nk, D), torch.bfloat16, 77.0)
     dvbuf, dv = guarded((B, Hkv, Nk, D), torch.bfloat16, 77.0)
-    ws = attn.alloc_bwd_workspace(B, Hq, Nq, D)
+    ws = attn.alloc_bwd_workspace(B, Hq, Nq, D, spill=spill, Nk=Nk)     # (spill: the form of the backward that stores dS)
+    ws.fill_(0xFF)
     rc = attn.tk_attn_fwd_rect(qd, kd, vd, o, lse, B, Hq, Hkv, Nq, Nk, D, causal, scale)
     assert rc == attn.TK_OK
     rc = attn.tk_attn_bwd_rect(qd, kd, vd, o, dod, lse, dq, dk, dv, B, Hq, Hkv, Nq, Nk, D, causal, scale, ws, ws.numel())

@@ -51,8 +51,9 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("spill", [False, True], ids=["recompute", "spill"])
 @pytest.mark.parametrize("B,Hq,Hkv,N,D,causal", CASES)
-def test_tail_forward_backward(attn, B, Hq, Hkv, N, D, causal):
+def test_tail_forward_backward(attn, B, Hq, Hkv, N, D, causal, spill):
     g = torch.Generator().manual_seed(20700 + N * 3 + D + Hq)
     q = torch.randn(B, Hq, N, D, generator=g).to(torch.bfloat16)
     k = torch.randn(B, Hkv, N, D, generator=g).to(torch.bfloat16)
@@ -66,7 +67,8 @@ def test_tail_forward_backward(attn, B, Hq, Hkv, N, D, causal):
     dqbuf, dq = guarded((B, Hq, N, D), torch.bfloat16, 77.0)
     dkbuf, dk = guarded((B, Hkv, N, D), torch.bfloat16, 77.0)
     dvbuf, dv = guarded((B, Hkv, N, D), torch.bfloat16, 77.0)
-    ws = attn.alloc_bwd_workspace(B, Hq, N, D)
+    ws = attn.alloc_bwd_workspace(B, Hq, N, D, spill=spill)     # (spill: the form of the backward that stores dS)
+    ws.fill_(0xFF)
     rc = attn.tk_attn_fwd_gqa(qd, kd, vd, o, lse, B, Hq, Hkv, N, D, causal, scale)
     assert rc == attn.TK_OK
     rc = attn.tk_attn_bwd_gqa(qd, kd, vd, o, dod, lse, dq, dk, dv, B, Hq, Hkv, N, D, causal, scale, ws, ws.numel())

@@ -1,7 +1,8 @@
 """The allocation-free backward entry point (tk_attn_bwd_noalloc) against tk_attn_bwd.
 
-Both run the same kernels; only the home of Delta differs (a scratch array inside the library's device
-image instead of a caller workspace), so the results must agree bit for bit.  Two calls in a row, the
+tk_attn_bwd with a Delta-only workspace runs the same kernels; only the home of Delta differs (a scratch
+array inside the library's device image instead of the caller's workspace), so the results must agree bit
+for bit.  Two calls in a row, the
 second on a smaller problem: the scratch keeps the first call's contents, which must not matter.
 """
 import math
@@ -24,7 +25,8 @@ def run_pair(attn, B, H, N, D, causal, seed):
     q, k, v, d_o = (torch.randn(B, H, N, D, generator=g).to(torch.bfloat16).cuda() for _ in range(4))
     scale = 1 / math.sqrt(D)
     o, lse = attn.attn_fwd(q, k, v, causal, scale)
-    ref = attn.attn_bwd(q, k, v, o, d_o, lse, causal, scale)
+    ws = attn.alloc_bwd_workspace(B, H, N, D, spill=False)     # the form of tk_attn_bwd that keeps only Delta
+    ref = attn.attn_bwd(q, k, v, o, d_o, lse, causal, scale, workspace=ws)
     out = [torch.full_like(q, 77.0) for _ in range(3)]
     print(f"launch tk_attn_bwd_noalloc B{B} H{H} N{N} D{D} causal={causal}", flush=True)
     rc = attn.tk_attn_bwd_noalloc(q, k, v, o, d_o, lse, *out, B, H, N, D, causal, scale)
