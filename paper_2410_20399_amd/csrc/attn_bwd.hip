@@ -855,42 +855,61 @@ hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const
 // ------------------------------------------------------------------------------------------
 template <int D>
 struct DqDsShape {
-    static constexpr int kWaves = 4;
-    static constexpr int kThreads = 256;
-    static constexpr int kTileQ = 128;                  // queries per workgroup (32 per wave)
-    static constexpr int kTileKV = 64;                  // keys per LDS stage
+    static constexpr int kWaves = 8;
+    static constexpr int kThreads = 512;
+    static constexpr int kTileQ = 256;                  // queries per workgroup (32 per wave)
+    static constexpr int kTileKV = 64;                  // keys per step
     static constexpr int kRowBytes = D * 2;
     static constexpr int kChunksPerRow = D / 8;
     static constexpr int kKTileBytes = kTileKV * kRowBytes;
-    static constexpr int kDsWaveBytes = 2 * 2048;       // two 32-key blocks of this wave's 32 queries
-    static constexpr int kStageBytes = kKTileBytes + kWaves * kDsWaveBytes;
-    static constexpr int kKLoads = kTileKV * kChunksPerRow / kThreads;   // per thread
-    static constexpr int kDsLoads = kDsWaveBytes / 1024;                  // per lane
+    static constexpr int kKStages = 4;                  // ring of K tiles, filled three tiles ahead
+    static constexpr int kDsTileBytes = 2 * 2048;       // the two 32-key blocks of one wave and one step
+    static constexpr int kDsAhead = 4;                  // dS tiles held in registers ahead of their use
+    static constexpr int kKLoads = kTileKV * kChunksPerRow / kThreads;   // per thread and tile
+    static constexpr int kDsLoads = kDsTileBytes / 1024;                  // per lane and tile
+    static constexpr int kLdsBytes = kKStages * kKTileBytes + kWaves * 2 * kDsTileBytes;
+    // vector-memory operations a wave issues per step, and how many of them are younger than the K tile
+    // that must have landed at the end of a step (see the loop)
+    static constexpr int kOpsPerStep = kKLoads + kDsLoads;
+    static constexpr int kWaitCount = kDsLoads + 2 * kOpsPerStep;
 };
 
-// dQ_i = scale * sum_j dS_ij K_j: one workgroup per 128-query tile (causal: balanced pairs of tiles), wave w
-// owns queries 32w..32w+31 and keeps dQ^T in registers while it walks 64-key tiles.  dQ^T += K^T dS^T needs
-// dS^T with the QUERY on lanes, and the stored blocks have the KEY on lanes: each wave pulls its own blocks
-// into LDS with direct loads and takes the operand out with transposing reads.  The 16-byte pieces of a
-// block are placed at (key * 4 + half * 2 + h) * 16 so that a transposing read (4 keys x 4 query quads per
-// 16 lanes) touches every bank once.  No mask code: kernel 2 stored zeros for masked pairs, padding
-// queries and padding keys, and a wave skips the tiles that lie wholly beyond its diagonal (which kernel 2
-// may not have written).
+// 16 bytes per lane from global memory into registers, issued through inline assembly so that the
+// compiler does not place a wait of its own before the first use: the data is only touched after the
+// loop's own wait (wait_vmcnt<>) and a claim_loaded() on the registers.
+__device__ __forceinline__ void load16_untracked(bf16x8& dst, const void* gptr) {
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(gptr) : "memory");
+}
+__device__ __forceinline__ void claim_loaded(bf16x8& r) { asm volatile("" : "+v"(r) : : "memory"); }
+
+// dQ_i = scale * sum_j dS_ij K_j: one workgroup per 256-query tile (causal: balanced pairs of tiles), wave w
+// owns queries 32w..32w+31 and keeps dQ^T in registers while the workgroup walks 64-key tiles.  The kernel is
+// bound by reading dS (2 bytes per query-key pair) from HBM, so everything is arranged around keeping many
+// bytes in flight: each wave loads its own dS blocks into registers four steps ahead (they are private to the
+// wave: no barrier is involved), K tiles go to a four-stage LDS ring by direct loads three steps ahead, and
+// the single wait per step is for a K tile that is older than three steps' worth of dS loads (the counter
+// retires in issue order), so those stay in flight across the barrier.
+// dQ^T += K^T dS^T needs dS^T with the QUERY on lanes, and the stored blocks have the KEY on lanes: a wave
+// writes the block it is about to use into a private LDS buffer, the 16-byte piece of (key, half, h) at
+// (key * 4 + half * 2 + h) * 16, and takes the operand out with transposing reads (4 keys x 4 query quads per
+// 16 lanes: every bank once).  No mask code: kernel 2 stored zeros for masked pairs, padding queries and
+// padding keys; a wave does not compute on tiles that lie wholly beyond its diagonal, which kernel 2 may not
+// have written: its loads of such tiles are redirected to its last real tile.
 template <int D, bool CAUSAL, bool TAIL>
-__global__ __launch_bounds__(256, 2)
+__global__ __launch_bounds__(512, 1)
 void attn_bwd_dq_from_ds_kernel(const bf16* __restrict__ K, const char* __restrict__ DS, bf16* __restrict__ dQ,
                                 int Nq, int Nk, int num_q_tiles, int total_wg, float scale, int hq, int hkv,
                                 int num_kv_tiles, int n_qb)
 {
     using S = DqDsShape<D>;
-    __shared__ __attribute__((aligned(1024))) char stage0[S::kStageBytes];
-    __shared__ __attribute__((aligned(1024))) char stage1[S::kStageBytes];
-
+    __shared__ __attribute__((aligned(1024))) char smem[S::kLdsBytes];
+    char* const kring = smem;
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     const int l32 = lane & 31;
     const int h = lane >> 5;
+    char* const dsbuf = smem + S::kKStages * S::kKTileBytes + wave * (2 * S::kDsTileBytes);   // two buffers of this wave
 
     const int units = CAUSAL ? (num_q_tiles + 1) / 2 : num_q_tiles;
     const int logical = xcd_remap(blockIdx.x, total_wg);
@@ -910,14 +929,8 @@ void attn_bwd_dq_from_ds_kernel(const bf16* __restrict__ K, const char* __restri
         int row = s / S::kChunksPerRow, pc = s % S::kChunksPerRow;
         k_src[it] = row * D + ((pc ^ swz<D>(row)) * 8);
     }
-    // dS block loads: LDS piece P = 64 * n + lane of a block holds (key P / 4, half (P / 2) % 2, h P % 2)
-    int ds_src[2];
-#pragma unroll
-    for (int n = 0; n < 2; n++) {
-        const int P = 64 * n + lane;
-        ds_src[n] = ((P >> 1) & 1) * 1024 + ((P & 1) * 32 + (P >> 2)) * 16;
-    }
-
+    // where this lane's 16-byte piece of a stored half-block goes in the wave's LDS buffer (half s adds 32)
+    const int piece_off = (l32 * 4 + h) * 16;
     // transposed operand from the K tile (A of dQ^T = K^T dS^T): rows 16*kk + 4h + j16/4 (+8)
     const int j16 = lane & 15;
     const int tr_row = 4 * h + (j16 >> 2);
@@ -933,35 +946,46 @@ void attn_bwd_dq_from_ds_kernel(const bf16* __restrict__ K, const char* __restri
     if (pass == 1 && qt == num_q_tiles - 1 - unit) break;   // odd tile count: the middle tile has no partner
     const int q0 = qt * S::kTileQ + wave * 32;
     const int my_q = q0 + l32;
-    const int qb = qt * 4 + wave;                    // this wave's query block
+    const int qb = qt * (S::kTileQ / 32) + wave;     // this wave's query block
 
-    auto issue_tile = [&](char* base, int tile) {
+    // 64-key tiles the workgroup walks (every key visible to its last query), rounded up to the unroll of the loop
+    int n_tiles;
+    if (!TAIL) {
+        n_tiles = (CAUSAL ? qt * S::kTileQ + S::kTileQ : Nk) / S::kTileKV;
+    } else {
+        int n_keys = Nk;
+        if (CAUSAL && qt * S::kTileQ + S::kTileQ + off < n_keys) n_keys = qt * S::kTileQ + S::kTileQ + off;
+        n_tiles = 2 * ((n_keys + 2 * S::kTileKV - 1) / (2 * S::kTileKV));
+    }
+    const int n_steps = (n_tiles + 3) & ~3;
+    // the last tile this wave computes on; -1: none (a wave of padding rows)
+    int last_tile = n_tiles - 1;
+    if (CAUSAL) { const int d = (q0 + 31 + off) / S::kTileKV; if (d < last_tile) last_tile = d; }
+    if (TAIL && q0 >= Nq) last_tile = -1;
+    // block (key tile 0, query block 0) of the head is always written: the stand-in for a wave without tiles
+    const char* ds_row = last_tile >= 0 ? DSh + (size_t)qb * 8192 : DSh;
+
+    auto issue_k = [&](int tile) {                   // into ring stage tile % 4
+        char* base = kring + (tile & (S::kKStages - 1)) * S::kKTileBytes + wave * 1024;
+        if (tile > n_tiles - 1) tile = n_tiles - 1;  // (beyond the walk: the last tile again, into a stage nobody reads any more)
         const int j0 = tile * S::kTileKV;
         const bf16* kt = Kh + (size_t)j0 * D;
-        if (!TAIL || j0 + S::kTileKV <= Nk) {
 #pragma unroll
-            for (int it = 0; it < S::kKLoads; it++)
-                load_global_to_lds16(kt + k_src[it], base + wave * 1024 + it * (S::kThreads * 16));
-        } else {
-#pragma unroll
-            for (int it = 0; it < S::kKLoads; it++) {
+        for (int it = 0; it < S::kKLoads; it++) {
+            int back = 0;
+            if (TAIL) {                              // rows >= Nk fetch row Nk-1 (their dS is 0)
                 const int row = j0 + (it * S::kThreads + tid) / S::kChunksPerRow;
-                const int back = (row < Nk ? 0 : row - (Nk - 1)) * D;   // rows >= Nk fetch row Nk-1 (their dS is 0)
-                load_global_to_lds16(kt + k_src[it] - back, base + wave * 1024 + it * (S::kThreads * 16));
+                back = (row < Nk ? 0 : row - (Nk - 1)) * D;
             }
+            load_global_to_lds16_untracked(kt + k_src[it] - back, base + it * (S::kThreads * 16));
         }
-        // the two 32-key blocks (waves 2*(tile%2), +1 of kernel 2) of key tile tile/2 for this wave's query block;
-        // a wave whose diagonal lies before this tile skips it: nothing may have been stored there
-        if (!(CAUSAL && j0 > q0 + 31 + off) && !(TAIL && q0 >= Nq)) {
-            const char* blk = DSh + (((size_t)(tile >> 1) * n_qb + qb) * 4 + 2 * (tile & 1)) * 2048;
-            char* dst = base + S::kKTileBytes + wave * S::kDsWaveBytes;
+    };
+    // the two 32-key blocks of step `tile` for this wave's queries: blocks 2*(tile%2), +1 of key tile tile/2
+    auto issue_ds = [&](bf16x8 (&r)[4], int tile) {
+        if (tile > last_tile) tile = last_tile < 0 ? 0 : last_tile;
+        const char* blk = ds_row + ((size_t)(tile >> 1) * n_qb * 4 + 2 * (tile & 1)) * 2048 + lane * 16;
 #pragma unroll
-            for (int c = 0; c < 2; c++)
-#pragma unroll
-                for (int n = 0; n < 2; n++)
-                    load_global_to_lds16(blk + c * 2048 + ds_src[n], dst + c * 2048 + n * 1024);
-        }
-        __builtin_amdgcn_sched_barrier(0);
+        for (int n = 0; n < 4; n++) load16_untracked(r[n], blk + n * 1024);
     };
 
     f32x16 dq_acc[D / 32];
@@ -970,11 +994,7 @@ void attn_bwd_dq_from_ds_kernel(const bf16* __restrict__ K, const char* __restri
 #pragma unroll
         for (int r = 0; r < 16; r++) dq_acc[db][r] = 0.f;
 
-    auto compute_tile = [&](const char* ks, int tile) {
-        const int j0 = tile * S::kTileKV;
-        if (CAUSAL && j0 > q0 + 31 + off) return;    // every key of the tile is masked for this wave
-        if (TAIL && q0 >= Nq) return;                // a wave of padding rows only
-        const char* dss = ks + S::kKTileBytes + wave * S::kDsWaveBytes;
+    auto compute_tile = [&](const char* ks, const char* dss) {
 #pragma unroll
         for (int kk = 0; kk < 4; kk++) {             // 16 keys per step
             const int ds_off = (kk >> 1) * 2048 + (kk & 1) * 1024;
@@ -992,27 +1012,44 @@ void attn_bwd_dq_from_ds_kernel(const bf16* __restrict__ K, const char* __restri
         }
     };
 
-    int n_tiles;
-    if (!TAIL) {
-        n_tiles = (CAUSAL ? qt * S::kTileQ + S::kTileQ : num_q_tiles * S::kTileQ) / S::kTileKV;
-    } else {
-        int n_keys = Nk;
-        if (CAUSAL && qt * S::kTileQ + S::kTileQ + off < n_keys) n_keys = qt * S::kTileQ + S::kTileQ + off;
-        n_tiles = 2 * ((n_keys + 2 * S::kTileKV - 1) / (2 * S::kTileKV));
+    // One step.  Issue order inside a step: the K tile three steps ahead, then the dS tile four steps ahead.
+    // At the end of step t the K tile of step t+1 must have landed; younger than it are the dS loads of its own
+    // step and everything of the two steps since: kWaitCount operations, which stay in flight.
+    bf16x8 set0[4], set1[4], set2[4], set3[4];
+    auto step = [&](bf16x8 (&r)[4], int t) {
+        char* dss = dsbuf + (t & 1) * S::kDsTileBytes;
+#pragma unroll
+        for (int n = 0; n < 4; n++) claim_loaded(r[n]);
+        // piece (block c = n / 2, half s = n % 2) of this lane -> its transposable place
+#pragma unroll
+        for (int n = 0; n < 4; n++) *(bf16x8*)(dss + (n >> 1) * 2048 + (n & 1) * 32 + piece_off) = r[n];
+        issue_k(t + 3);
+        issue_ds(r, t + 4);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t <= last_tile) compute_tile(kring + (t & (S::kKStages - 1)) * S::kKTileBytes, dss);
+        __builtin_amdgcn_sched_barrier(0);
+        wait_vmcnt_lds_done<S::kWaitCount>();
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // prologue in the loop's own issue order (steps -4 .. -1 without their computation)
+    issue_ds(set0, 0);
+    issue_k(0); issue_ds(set1, 1);
+    issue_k(1); issue_ds(set2, 2);
+    issue_k(2); issue_ds(set3, 3);
+    wait_vmcnt<S::kWaitCount>();
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll 1
+    for (int t = 0; t < n_steps; t += 4) {
+        step(set0, t);
+        step(set1, t + 1);
+        step(set2, t + 2);
+        step(set3, t + 3);
     }
-    issue_tile(stage0, 0);
-    wait_vmcnt<0>();
-    __syncthreads();
-    for (int t = 0; t < n_tiles; t += 2) {
-        issue_tile(stage1, t + 1);
-        compute_tile(stage0, t);
-        wait_vmcnt<0>();
-        __syncthreads();
-        if (t + 2 < n_tiles) issue_tile(stage0, t + 2);
-        compute_tile(stage1, t + 1);
-        wait_vmcnt<0>();
-        __syncthreads();
-    }
+    wait_vmcnt<0>();          // the redirected loads of the last steps must not outlive this pass (LDS, registers)
+    __builtin_amdgcn_s_barrier();
 
     if (!TAIL || my_q < Nq) {
         bf16* dQr = dQ + head + (size_t)my_q * D;
@@ -1033,10 +1070,11 @@ static hipError_t launch_dq_from_ds_tt(const void* k, const void* ds, void* dq,
                                        int B, int H, int Hkv, int Nq, int Nk, float scale, hipStream_t stream)
 {
     using S = DqDsShape<D>;
+    auto kern = attn_bwd_dq_from_ds_kernel<D, CAUSAL, TAIL>;
     const int num_q_tiles = (Nq + S::kTileQ - 1) / S::kTileQ;
     const int num_kv_tiles = (Nk + 127) / 128;
     const int total = B * H * (CAUSAL ? (num_q_tiles + 1) / 2 : num_q_tiles);
-    hipLaunchKernelGGL((attn_bwd_dq_from_ds_kernel<D, CAUSAL, TAIL>), dim3(total), dim3(S::kThreads), 0, stream,
+    hipLaunchKernelGGL(kern, dim3(total), dim3(S::kThreads), 0, stream,
                        (const bf16*)k, (const char*)ds, (bf16*)dq, Nq, Nk, num_q_tiles, total, scale, H, Hkv,
                        num_kv_tiles, ds_query_blocks(Nq));
     return hipGetLastError();
@@ -1046,7 +1084,7 @@ template <int D>
 static hipError_t launch_dq_from_ds_t(const void* k, const void* ds, void* dq,
                                       int B, int H, int Hkv, int Nq, int Nk, int causal, float scale, hipStream_t stream)
 {
-    const bool tail = Nq != Nk || Nq % 128;
+    const bool tail = Nq != Nk || Nq % 256;
     if (causal) return tail ? launch_dq_from_ds_tt<D, true, true>(k, ds, dq, B, H, Hkv, Nq, Nk, scale, stream)
                             : launch_dq_from_ds_tt<D, true, false>(k, ds, dq, B, H, Hkv, Nq, Nk, scale, stream);
     return tail ? launch_dq_from_ds_tt<D, false, true>(k, ds, dq, B, H, Hkv, Nq, Nk, scale, stream)
