@@ -337,8 +337,16 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
 #pragma unroll
         for (int i = 0; i < kSteps; i++) { set_b.tq[i] = zero; set_b.tdo[i] = zero; }
         set_b.pb[0] = set_b.pb[1] = set_b.dsb[0] = set_b.dsb[1] = zero;
+        if (SPILL) set_a.dsb[0] = set_a.dsb[1] = zero;      // (what the first step of the pass stores when nothing is deferred)
     }
     f32x4 lse4[4], dl4[4];
+    // SPILL: where the dS block held in the previous step's fragment set goes (see step()); at the start of
+    // a pass that set is all zeros and the address is the pass's own first block
+    char* ds_pending = nullptr;
+    if (SPILL) {
+        const size_t q_head = (size_t)(bh / hkv) * hq + (size_t)(bh % hkv) * group;
+        ds_pending = DS + ((q_head * num_kv_tiles + kt) * n_qb + i_begin / S::kTileQ) * (size_t)8192 + wave * 2048;
+    }
 
     auto read_rows = [&](const char* qs, int kb) {
         rq[kb] = lds_read_b128(qs, row_lane ^ ((2 * kb) << 4));
@@ -397,6 +405,16 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
             if (kb < 4) { lse4[kb] = stat[2 * kb + h]; dl4[kb] = stat[8 + 2 * kb + h]; }
             __builtin_amdgcn_sched_barrier(0);
         }
+        // SPILL: the PREVIOUS block's dS leaves here, one step after it was formed (stored right after its
+        // conversion it costs ~10 % more cycles per step: every score of the block has to be finished first).
+        // Every step issues exactly these two stores - the waits below count them; the first step of a pass
+        // writes the zeros of the fresh fragment set to its own block, which the next step overwrites.
+        if (SPILL) {
+            *(bf16x8*)(ds_pending + lane * 16) = prev.dsb[0];
+            *(bf16x8*)(ds_pending + 1024 + lane * 16) = prev.dsb[1];
+            ds_pending = ds_head + ((size_t)(i0 / S::kTileQ) * 4 + wave) * 2048;     // this block (wave-uniform)
+            __builtin_amdgcn_sched_barrier(0);
+        }
 
         // ---- phase 2 (this block's P, dS) interleaved with phase 3 of the PREVIOUS block
         // (dV^T += dO^T P, dK^T += Q^T dS) and with the reads of the next block's row fragments
@@ -431,11 +449,6 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
             cur.pb[ks] = cvt8(s[r0], s[r0 + 1], s[r0 + 2], s[r0 + 3], s[r0 + 4], s[r0 + 5], s[r0 + 6], s[r0 + 7]);
             cur.dsb[ks] = cvt8(dp[r0], dp[r0 + 1], dp[r0 + 2], dp[r0 + 3], dp[r0 + 4], dp[r0 + 5], dp[r0 + 6], dp[r0 + 7]);
         }
-        if (SPILL) {
-            char* blk_ptr = ds_head + ((size_t)(i0 / S::kTileQ) * 4 + wave) * 2048;     // wave-uniform
-            *(bf16x8*)(blk_ptr + lane * 16) = cur.dsb[0];
-            *(bf16x8*)(blk_ptr + 1024 + lane * 16) = cur.dsb[1];
-        }
 #pragma unroll
         for (int idx = 0; idx < kSteps; idx++) {
             late_products(prev, idx);
@@ -454,7 +467,7 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         // more load per block).  The wave's own LDS reads of this block's stage must have returned as
         // well: after the barrier the next step's prefetch overwrites that stage.
         // (the counter retires loads and stores in issue order: the two dS stores of this step and of the
-        // previous one are younger than the loads waited for)
+        // previous one were issued after the loads waited for)
         constexpr int kStores = SPILL ? 4 : 0;
         if (wave == 0) wait_vmcnt_lds_done<(S::kAhead - 2) * (S::kLoadsPerBlock + 1) + kStores>();
         else wait_vmcnt_lds_done<(S::kAhead - 2) * S::kLoadsPerBlock + kStores>();
@@ -511,6 +524,12 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     if (kDeferred) {
 #pragma unroll
         for (int idx = 0; idx < kSteps; idx++) late_products(set_b, idx);
+    }
+    // ... and its dS (the block count of a pass is even: the last step wrote set_b, or set_a when nothing is deferred)
+    if (SPILL) {
+        const Late& last = kDeferred ? set_b : set_a;
+        *(bf16x8*)(ds_pending + lane * 16) = last.dsb[0];
+        *(bf16x8*)(ds_pending + 1024 + lane * 16) = last.dsb[1];
     }
 
     // ---- epilogue.  In accumulator layout a lane holds 4 consecutive columns of ONE key row
