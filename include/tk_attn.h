@@ -292,7 +292,10 @@ int tk_attn_decode_plan(int B, int Hq, int Hkv, int Nk, int D, int compute_units
  * accumulation and one rounding to bf16.
  *
  *   a : in,  bf16 [M, K] row-major        b : in, bf16 [K, N] row-major        c : out, bf16 [M, N] row-major
- * M and N must be positive multiples of 256, K a positive multiple of 64 (TK_ERR_BAD_DIM otherwise).
+ * M >= 1; N and K positive multiples of 8, so that every row starts on a 16-byte boundary
+ * (TK_ERR_BAD_DIM otherwise).  The kernel works on 256 x 256 x 64 tiles; shapes that are not multiples
+ * of those run a variant that masks the edge tiles (rows and columns past the end are not stored, the
+ * part of the last K step past K contributes zeros).
  * No workspace; the result is bit-reproducible (every element is one fixed-order accumulation).
  */
 int tk_gemm(const void* a, const void* b, void* c, int M, int N, int K, void* stream);

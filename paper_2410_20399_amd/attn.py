@@ -437,7 +437,7 @@ def rotary(x, sin_table, cos_table, out=None, stream=None):
 
 
 def gemm(a, b, out=None, stream=None):
-    """C = A B: a bf16 [M,K], b bf16 [K,N] -> c bf16 [M,N] (M, N multiples of 256, K of 64)."""
+    """C = A B: a bf16 [M,K], b bf16 [K,N] -> c bf16 [M,N] (N and K multiples of 8)."""
     if a.dtype != torch.bfloat16 or b.dtype != torch.bfloat16 or a.dim() != 2 or b.dim() != 2:
         raise ValueError("a, b must be 2-D bf16 tensors")
     if not (a.is_cuda and b.is_cuda and a.is_contiguous() and b.is_contiguous()) or a.shape[1] != b.shape[0]:

@@ -33,9 +33,18 @@ struct GemmShape {
     static constexpr int kSuperM = 8;                             // tile rows walked together (L2 reuse of the B panels)
 };
 
+// sixteen zero bytes: the source of the A chunks that lie beyond K in an edge tile
+__device__ __attribute__((aligned(16))) const bf16 g_gemm_zero[8] = {};
+
 __device__ __forceinline__ int gemm_swz_a(int row) { return (row >> 1) & 7; }
 __device__ __forceinline__ int gemm_swz_b(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
+// EDGE: the general case (M not a multiple of 256, N not of 256, or K not of 64; N and K multiples of 8
+// so that every row starts on a 16-byte boundary).  The kernel still works on whole 256 x 256 x 64 tiles:
+// rows of A past M fetch row M-1 and columns of B past N fetch the last 8 columns (their results are never
+// stored), the chunks of A and the rows of B past K are fetched from a block of zeros so that they add
+// nothing, and rows / columns past the end are not stored.  The aligned case compiles without any of this.
+template <bool EDGE>
 __global__ __launch_bounds__(256, 1)
 void gemm_kernel(const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* __restrict__ C,
                  int M, int N, int K, int tiles_m, int tiles_n)
@@ -84,17 +93,41 @@ void gemm_kernel(const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* _
     }
     auto issue_stage = [&](int step) {
         char* base = ring + (step & 1) * S::kStageBytes + wave * 1024;
-        const bf16* a = A + (size_t)step * S::kTileK;
-        const bf16* b = B + (size_t)step * S::kTileK * N;
+        if (!EDGE) {
+            const bf16* a = A + (size_t)step * S::kTileK;
+            const bf16* b = B + (size_t)step * S::kTileK * N;
 #pragma unroll
-        for (int it = 0; it < S::kALoads; it++)
-            load_global_to_lds16_untracked(a + a_src[it], base + it * (S::kThreads * 16));
+            for (int it = 0; it < S::kALoads; it++)
+                load_global_to_lds16_untracked(a + a_src[it], base + it * (S::kThreads * 16));
 #pragma unroll
-        for (int t = 0; t < 2; t++)
+            for (int t = 0; t < 2; t++)
 #pragma unroll
-            for (int it = 0; it < S::kBLoads; it++)
-                load_global_to_lds16_untracked(b + b_src[it] + 128 * t,
-                                               base + S::kABytes + t * S::kBHalfBytes + it * (S::kThreads * 16));
+                for (int it = 0; it < S::kBLoads; it++)
+                    load_global_to_lds16_untracked(b + b_src[it] + 128 * t,
+                                                   base + S::kABytes + t * S::kBHalfBytes + it * (S::kThreads * 16));
+        } else {
+            const int k0 = step * S::kTileK;
+#pragma unroll
+            for (int it = 0; it < S::kALoads; it++) {
+                const int s = it * S::kThreads + tid, row = s >> 3, pc = s & 7;
+                size_t r = m0 + row;
+                if (r > (size_t)M - 1) r = (size_t)M - 1;
+                const int k = k0 + ((pc ^ gemm_swz_a(row)) << 3);
+                const bf16* src = k < K ? A + r * K + k : g_gemm_zero;
+                load_global_to_lds16_untracked(src, base + it * (S::kThreads * 16));
+            }
+#pragma unroll
+            for (int t = 0; t < 2; t++)
+#pragma unroll
+                for (int it = 0; it < S::kBLoads; it++) {
+                    const int s = it * S::kThreads + tid, row = s >> 4, pc = s & 15;
+                    const int k = k0 + row;
+                    size_t col = n0 + 128 * t + ((pc ^ gemm_swz_b(row)) << 3);
+                    if (col > (size_t)N - 8) col = (size_t)N - 8;
+                    const bf16* src = k < K ? B + (size_t)k * N + col : g_gemm_zero;
+                    load_global_to_lds16_untracked(src, base + S::kABytes + t * S::kBHalfBytes + it * (S::kThreads * 16));
+                }
+        }
     };
 
     // ---- per-lane LDS read offsets
@@ -150,7 +183,7 @@ void gemm_kernel(const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* _
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    const int n_steps = K / S::kTileK;
+    const int n_steps = (K + S::kTileK - 1) / S::kTileK;
     issue_stage(0);
     if (n_steps > 1) issue_stage(1);
     if (n_steps > 1) wait_vmcnt<S::kLoadsPerStage>(); else wait_vmcnt<0>();
@@ -185,14 +218,18 @@ void gemm_kernel(const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* _
     // ---- epilogue: lane <-> row of C; register r of block (b, a) <-> column 32b + 8*(r/4) + 4h + r%4
 #pragma unroll
     for (int a = 0; a < 4; a++) {
-        bf16* crow = C + (m0 + wm * 128 + 32 * a + l32) * N + n0 + wn * 128;
+        const size_t row = m0 + wm * 128 + 32 * a + l32;
+        if (EDGE && row >= (size_t)M) continue;
+        bf16* crow = C + row * N + n0 + wn * 128;
 #pragma unroll
         for (int b = 0; b < 4; b++)
 #pragma unroll
             for (int g = 0; g < 4; g++) {
+                const int col = 32 * b + 8 * g + 4 * h;      // within the wave's 128 columns; N is a multiple of 8
+                if (EDGE && n0 + wn * 128 + col >= (size_t)N) continue;
                 bf16x2 lo = cvt2(acc[b][a][4 * g + 0], acc[b][a][4 * g + 1]);
                 bf16x2 hi = cvt2(acc[b][a][4 * g + 2], acc[b][a][4 * g + 3]);
-                *(bf16x4*)(crow + 32 * b + 8 * g + 4 * h) = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+                *(bf16x4*)(crow + col) = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
             }
     }
 }
@@ -200,9 +237,14 @@ void gemm_kernel(const bf16* __restrict__ A, const bf16* __restrict__ B, bf16* _
 hipError_t launch_gemm(const void* a, const void* b, void* c, int M, int N, int K, hipStream_t stream)
 {
     using S = GemmShape;
-    const int tiles_m = M / S::kTileM, tiles_n = N / S::kTileN;
-    hipLaunchKernelGGL(gemm_kernel, dim3(tiles_m * tiles_n), dim3(S::kThreads), 0, stream,
-                       (const bf16*)a, (const bf16*)b, (bf16*)c, M, N, K, tiles_m, tiles_n);
+    const int tiles_m = (M + S::kTileM - 1) / S::kTileM, tiles_n = (N + S::kTileN - 1) / S::kTileN;
+    const bool edge = M % S::kTileM || N % S::kTileN || K % S::kTileK;
+    if (edge)
+        hipLaunchKernelGGL(gemm_kernel<true>, dim3(tiles_m * tiles_n), dim3(S::kThreads), 0, stream,
+                           (const bf16*)a, (const bf16*)b, (bf16*)c, M, N, K, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL(gemm_kernel<false>, dim3(tiles_m * tiles_n), dim3(S::kThreads), 0, stream,
+                           (const bf16*)a, (const bf16*)b, (bf16*)c, M, N, K, tiles_m, tiles_n);
     return hipGetLastError();
 }
 

@@ -396,8 +396,8 @@ size_t tk_attn_bwd_noalloc_max_rows(void) { return kNoallocScratchFloats; }
 int tk_gemm(const void* a, const void* b, void* c, int M, int N, int K, void* stream)
 {
     if (!a || !b || !c) return TK_ERR_NULL_PTR;
-    if (M < 256 || N < 256 || K < 64 || M % 256 || N % 256 || K % 64) return TK_ERR_BAD_DIM;
-    if ((long long)(M / 256) * (N / 256) > 0x7fffffffLL) return TK_ERR_BAD_DIM;
+    if (M < 1 || N < 8 || K < 8 || N % 8 || K % 8) return TK_ERR_BAD_DIM;     // every row of A, B and C starts on 16 bytes
+    if ((long long)((M + 255) / 256) * ((N + 255) / 256) > 0x7fffffffLL) return TK_ERR_BAD_DIM;
     if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return TK_ERR_MISALIGNED;
     hipError_t e = tk::launch_gemm(a, b, c, M, N, K, (hipStream_t)stream);
     return e == hipSuccess ? TK_OK : TK_ERR_LAUNCH;

@@ -67,7 +67,7 @@ hipError_t launch_attn_bwd_dq(const void* q, const void* k, const void* v, const
                               int B, int H, int Hkv, int Nq, int Nk, int D, int causal, float scale, hipStream_t stream,
                               const void* o = nullptr, float* delta_out = nullptr);
 
-// bf16 matrix multiply C = A B: A [M,K], B [K,N], C [M,N] row-major; M, N multiples of 256, K of 64
+// bf16 matrix multiply C = A B: A [M,K], B [K,N], C [M,N] row-major; M >= 1, N and K multiples of 8
 hipError_t launch_gemm(const void* a, const void* b, void* c, int M, int N, int K, hipStream_t stream);
 
 // rotary positional encoding: x, o [B,H,N,D]; sin, cos [N, D/2]

@@ -282,7 +282,8 @@ def test_gemm_rejects_bad_arguments(lib):
         assert lib.tk_gemm(*ptrs, 256, 256, 64, None) == a.TK_ERR_NULL_PTR
         ptrs[i] = ODD
         assert lib.tk_gemm(*ptrs, 256, 256, 64, None) == a.TK_ERR_MISALIGNED
-    for M, N, K in ((0, 256, 64), (128, 256, 64), (256, 300, 64), (256, 256, 32), (256, 256, 100), (-256, 256, 64)):
+    # M >= 1; N and K positive multiples of 8 (rows must start on 16 bytes)
+    for M, N, K in ((0, 256, 64), (256, 300, 64), (256, 4, 64), (256, 256, 4), (256, 256, 100), (-256, 256, 64), (256, 0, 64)):
         assert lib.tk_gemm(P, P, P, M, N, K, None) == a.TK_ERR_BAD_DIM, (M, N, K)
 
 

@@ -39,6 +39,25 @@ def test_gemm_small_full(attn, M, N, K):
     assert (err <= tol(ref, K)).all(), float((err - tol(ref, K)).max())
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 8, 8), (5, 24, 40), (255, 264, 72), (257, 248, 200), (300, 520, 1000), (1000, 1000, 1000),
+                                   (256, 256, 56), (513, 256, 64), (256, 776, 128)])
+def test_gemm_edge_tiles(attn, M, N, K):
+    """Shapes that are not multiples of the 256 x 256 x 64 tile: every element against the oracle, and the
+    memory after C untouched (rows and columns past the end are masked, not clipped by luck)."""
+    a, b = make(M, N, K, 1840 + M + N + K)
+    print(f"launch gemm edge M{M} N{N} K{K}", flush=True)
+    guard = 4096
+    buf = torch.full((M * N + guard,), 77.0, dtype=torch.bfloat16, device="cuda")
+    c = buf[:M * N].view(M, N)
+    attn.gemm(a.cuda(), b.cuda(), out=c)
+    torch.cuda.synchronize()
+    assert bool((buf[M * N:] == 77.0).all()), "wrote past the end of C"
+    ref = orc.gemm(a.double().numpy(), b.double().numpy())
+    err = np.abs(c.cpu().double().numpy() - ref)
+    assert np.isfinite(err).all()
+    assert (err <= tol(ref, K)).all(), float((err - tol(ref, K)).max())
+
+
 def test_gemm_full_size_sampled_and_reproducible(attn):
     M = N = K = 8192
     a, b = make(M, N, K, 8192)
