@@ -80,14 +80,18 @@ struct DkdvShape {
     static constexpr int kThreads = 256;
     static constexpr int kTileKV = 128;                 // keys per workgroup (32 per wave)
     static constexpr int kTileQ = 32;                   // queries per loop iteration
-    static constexpr int kStages = 4;                   // LDS ring of query blocks (a power of two), filled kStages-1 blocks ahead
+    // LDS ring of query blocks.  D = 64: four stages, filled three blocks ahead.  D = 128 (the pipelined
+    // step, see the kernel): seven stages, six of them filled at the start; step n then fetches block n + 6
+    // into the stage of block n - 1, which nobody reads any more.
+    static constexpr bool kPipe = (D == 128);
+    static constexpr int kStages = kPipe ? 7 : 4;
     static constexpr int kAhead = kStages - 1;
     static constexpr int kRowBytes = D * 2;
     static constexpr int kChunksPerRow = D / 8;
     static constexpr int kQTileBytes = kTileQ * kRowBytes;
     static constexpr int kStageBytes = 2 * kQTileBytes + 256;      // Q, dO, LSE[32], Delta[32]; a multiple of 256
     static constexpr int kQLoads = kTileQ * kChunksPerRow / kThreads;   // per thread, per tensor
-    static constexpr int kLoadsPerBlock = 2 * kQLoads;  // per thread (wave 0 issues one more, for the statistics)
+    static constexpr int kLoadsPerBlock = 2 * kQLoads;  // per thread, of Q and dO rows (one more load fetches the statistics)
     static constexpr int kEpiPitch = kRowBytes + 8;     // row pitch of the epilogue staging tile: the odd multiple of 8 bytes spreads
                                                         // both the 8-byte column-piece writes and the row reads over the banks
 };
@@ -196,75 +200,97 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         q_src[it] = row * D + ((pc ^ swz<D>(row)) * 8);
     }
     // Producer side of the ring: a cursor over the query blocks of this workgroup's passes, in the
-    // order the passes consume them.  Every call issues the same number of loads (the vmcnt waits
-    // below count them); once the walk is exhausted it fetches the spare block again into a
-    // stage nobody reads.
+    // order the passes consume them.  Every call issues the same number of loads in every wave (the
+    // vmcnt waits below count them); once the walk is exhausted it fetches one block again and again
+    // into stages nobody reads.
     // The lengths need not be multiples of the tile sizes: the kernel works on padded sequences.
     // Reads of rows past the end are redirected to the last row; a query row >= Nq gets LSE = +inf,
     // so its P and dS are exactly 0; key rows >= Nk are computed like any other and not stored.
-    int p_vu = blockIdx.x, p_half = 0, p_blk = 0, p_nblocks = 0, p_g = 0, p_ibegin = 0;
+    int p_vu = blockIdx.x, p_half = 0, p_nblocks = 0, p_g = 0, p_ibegin = 0;
     size_t p_head_row = 0;                  // first row of the group's first query head of the producer's pass
-    size_t spare_head_row = 0;
-    int spare_i0 = 0;
-    int p_count = 0;                        // blocks issued so far (selects the ring stage)
-    auto producer_open = [&]() {            // set the cursor to the first block of pass (p_vu, p_half)
+    size_t p_row = 0;                       // first row of the next block to fetch (rows of all heads counted through)
+    int p_i0 = 0;                           // ... and its first query within its head
+    int p_left = 0;                         // blocks left in the current head's run, this one included
+    int p_advance = S::kTileQ;              // rows from one block to the next (0 once the walk is exhausted)
+    int p_stage = 0;                        // byte offset of the ring stage the next block goes to
+    auto next_stage = [&](int off) { return off + S::kStageBytes == S::kStages * S::kStageBytes ? 0 : off + S::kStageBytes; };
+    auto producer_head = [&]() __attribute__((always_inline)) {            // the cursor at the first block of query head p_g of the pass
+        p_row = p_head_row + (size_t)p_g * Nq + p_ibegin;
+        p_i0 = p_ibegin;
+        p_left = p_nblocks;
+    };
+    auto producer_open = [&]() __attribute__((always_inline)) {            // set the cursor to the first block of pass (p_vu, p_half)
         int bh, kt;
         pass_tile(p_vu, p_half, bh, kt);
         p_ibegin = pass_ibegin(kt);
         p_head_row = q_head_row(bh);
         p_nblocks = pass_nblocks(p_ibegin);
-        p_blk = 0;
         p_g = 0;
+        producer_head();
+    };
+    // the end of a head's run: rare, so that the steady state of prepare() below is straight-line scalar code
+    auto producer_turn = [&]() __attribute__((always_inline)) {
+        if (++p_g < group) { producer_head(); return; }
+        next_pass(p_vu, p_half);
+        if (p_vu < total_units) { producer_open(); return; }
+        p_row -= p_advance;                 // exhausted: stay on the last block
+        p_i0 -= p_advance;
+        p_advance = 0;
+        p_left = 0x7fffffff;
+    };
+    // A block's fetch is split into prepare() (the cursor: scalar work, one rare branch) and its loads,
+    // emit(0 .. kLoadsPerBlock): the pipelined step spreads the loads over its matrix instructions, because
+    // the compute unit's address unit takes one 16-byte-per-lane instruction every ~16 cycles and a wave
+    // that issues several in a row stalls on it.
+    size_t e_head_row = 0, e_row = 0;       // of the block being fetched: first row of its head; its own first row
+    int e_i0 = 0, e_stage = 0;              // its first query within the head; byte offset of its ring stage
+    auto prepare = [&]() __attribute__((always_inline)) {
+        e_row = p_row;
+        e_i0 = p_i0;
+        e_head_row = p_row - p_i0;
+        e_stage = p_stage;
+        p_stage = next_stage(p_stage);
+        p_row += p_advance;
+        p_i0 += p_advance;
+        --p_left;
+    };
+    // (kept apart from prepare(): the pipelined step calls prepare() in the middle of a long basic block,
+    // which this branch would split)
+    auto prepare_turn = [&]() __attribute__((always_inline)) {
+        if (__builtin_expect(p_left == 0, 0)) producer_turn();
+    };
+    auto emit = [&](int which) {
+        char* base = ring + e_stage;
+        if (which < S::kLoadsPerBlock) {        // Q rows, then dO rows
+            const int it = which % S::kQLoads;
+            const bf16* src = (which < S::kQLoads ? Q : dO) + e_row * D + q_src[it];
+            char* dst = base + (which < S::kQLoads ? 0 : S::kQTileBytes) + it * (S::kThreads * 16) + wave * 1024;
+            if (TAIL) {
+                // a block that runs past the last query: rows >= Nq fetch row Nq-1 instead
+                const int r = e_i0 + (it * S::kThreads + tid) / S::kChunksPerRow;
+                src -= (r < Nq ? 0 : r - (Nq - 1)) * D;
+            }
+            load_global_to_lds16_untracked(src, dst);
+        } else if (TAIL) {
+            // The statistics: every wave fetches them, to the same place (the same bytes four times over cost
+            // nothing; a branch on the wave number costs every wave a restart of its instruction stream, and
+            // the waits would have to count differently per wave).
+            // lanes 0..31 fetch LSE of the block's 32 queries, lanes 32..63 their Delta
+            const int r = e_i0 + l32;
+            const float* src = (lane < 32) ? (r < Nq ? LSE + e_head_row + r : g_lse_pad)
+                                           : Delta + e_head_row + (r < Nq ? r : Nq - 1);
+            load_global_to_lds4_untracked(src, base + 2 * S::kQTileBytes);
+        } else {
+            // 8 lanes fetch LSE[row..row+31], 8 lanes Delta[row..row+31], 16 bytes each; the other lanes are masked off
+            const float* src = (lane < 8) ? (LSE + e_row + lane * 4) : (Delta + e_row + (lane - 8) * 4);
+            load_global_to_lds16_lanes16_untracked(src, base + 2 * S::kQTileBytes);
+        }
     };
     auto issue_next = [&]() {
-        const bool live = p_vu < total_units;
-        const size_t head_row = live ? p_head_row + (size_t)p_g * Nq : spare_head_row;
-        const int i0 = live ? p_ibegin + p_blk * S::kTileQ : spare_i0;      // first query of the block, within its head
-        const size_t row = head_row + i0;
-        char* base = ring + (p_count & (S::kStages - 1)) * S::kStageBytes;
-        if (!TAIL || i0 + S::kTileQ <= Nq) {
+        prepare();
 #pragma unroll
-            for (int it = 0; it < S::kQLoads; it++)
-                load_global_to_lds16_untracked(Q + row * D + q_src[it], base + it * (S::kThreads * 16) + wave * 1024);
-#pragma unroll
-            for (int it = 0; it < S::kQLoads; it++)
-                load_global_to_lds16_untracked(dO + row * D + q_src[it],
-                                               base + S::kQTileBytes + it * (S::kThreads * 16) + wave * 1024);
-        } else {
-            // the block runs past the last query: rows >= Nq fetch row Nq-1 instead
-#pragma unroll
-            for (int it = 0; it < S::kQLoads; it++) {
-                const int r = i0 + (it * S::kThreads + tid) / S::kChunksPerRow;
-                const int back = (r < Nq ? 0 : r - (Nq - 1)) * D;       // elements to step back
-                load_global_to_lds16_untracked(Q + row * D + q_src[it] - back, base + it * (S::kThreads * 16) + wave * 1024);
-            }
-#pragma unroll
-            for (int it = 0; it < S::kQLoads; it++) {
-                const int r = i0 + (it * S::kThreads + tid) / S::kChunksPerRow;
-                const int back = (r < Nq ? 0 : r - (Nq - 1)) * D;
-                load_global_to_lds16_untracked(dO + row * D + q_src[it] - back,
-                                               base + S::kQTileBytes + it * (S::kThreads * 16) + wave * 1024);
-            }
-        }
-        if (TAIL) {
-            if (wave == 0) {   // lanes 0..31 fetch LSE of the block's 32 queries, lanes 32..63 their Delta
-                const int r = i0 + l32;
-                const float* src = (lane < 32) ? (r < Nq ? LSE + head_row + r : g_lse_pad)
-                                               : Delta + head_row + (r < Nq ? r : Nq - 1);
-                load_global_to_lds4_untracked(src, base + 2 * S::kQTileBytes);
-            }
-        } else if (wave == 0 && lane < 16) {   // 8 lanes fetch LSE[row..row+31], 8 lanes Delta[row..row+31], 16 bytes each
-            const float* src = (lane < 8) ? (LSE + row + lane * 4) : (Delta + row + (lane - 8) * 4);
-            load_global_to_lds16_untracked(src, base + 2 * S::kQTileBytes);
-        }
-        p_count++;
-        if (live && ++p_blk == p_nblocks) {
-            p_blk = 0;
-            if (++p_g == group) {
-                next_pass(p_vu, p_half);
-                if (p_vu < total_units) producer_open();
-            }
-        }
+        for (int which = 0; which <= S::kLoadsPerBlock; which++) emit(which);
+        prepare_turn();
     };
 
     // ---- per-lane LDS offsets
@@ -275,10 +301,6 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     const int trq_lane = trq_row * S::kRowBytes + (((2 * ghalf + ((j16 & 3) >> 1)) ^ swz<D>(trq_row)) << 4) + ((j16 & 1) << 3);
 
     constexpr int kSteps = D / 16;          // MFMA steps of S / dP; also 2 * (D/32) steps of dV^T / dK^T
-    // D = 128: one wave per SIMD, the dV^T / dK^T products of a block run one block late (next to the
-    // following block's vector work).  D = 64: the registers allow two waves per SIMD, which overlap
-    // each other's matrix and vector phases, and the products run in their own block.
-    constexpr bool kDeferred = (D == 128);
     bf16x8 kf[D / 16], vf[D / 16];          // K, V fragments of this wave's 32 keys (B operands of S = Q K^T and dP = dO V^T)
     auto load_kv = [&](int bh, int kt) {
         const int key = kt * S::kTileKV + wave * 32 + l32;
@@ -291,13 +313,11 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     };
 
     int c_vu = blockIdx.x, c_half = 0;      // consumer side: the pass being computed (the grid never exceeds the unit count)
-    int c_count = 0;                        // blocks consumed so far (selects the ring stage)
+    int c_stage = 0;                        // byte offset of the ring stage of the next block to consume
     {
         int bh, kt;
         pass_tile(c_vu, c_half, bh, kt);
         producer_open();
-        spare_head_row = p_head_row;
-        spare_i0 = p_ibegin;
 #pragma unroll
         for (int b = 0; b < S::kAhead; b++) issue_next();
         load_kv(bh, kt);
@@ -316,8 +336,6 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     // blocks that may hold a masked (query, key) pair: rows below j0 + 127 - off, i.e. four blocks
     // from i_begin when that is the tile's own first row, up to five when off is not a multiple of 32
     const int n_masked = !CAUSAL ? 0 : !TAIL ? 4 : (n_blocks < 6 ? n_blocks : 6);
-    spare_head_row = q_head_row(bh);
-    spare_i0 = i_begin;
 
     f32x16 dk_acc[D / 32], dv_acc[D / 32];
 #pragma unroll
@@ -325,69 +343,265 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
 #pragma unroll
         for (int r = 0; r < 16; r++) { dk_acc[db][r] = 0.f; dv_acc[db][r] = 0.f; }
 
-    bf16x8 rq[kSteps], rdo[kSteps];         // row fragments of the block about to be computed
-    // transposed fragments [ks * (D/32) + db] and bf16 P / dS of a block; two sets, because the
-    // dV^T / dK^T products of a block are issued one iteration late (see the loop)
-    struct Late { bf16x8 tq[kSteps], tdo[kSteps], pb[2], dsb[2]; };
-    Late set_a, set_b;
-    {
-        bf16x8 zero;
+    // Every global load so far (this pass's K, V fragments, its first blocks, the previous pass's
+    // stores) completes here.  The empty asm statements pin the fragment loads above this point (the
+    // compiler would otherwise sink them to their first use inside the loop and wait for them there,
+    // draining the prefetch every iteration): inside the loop the only waits on the vector memory
+    // counter are the explicit ones, which leave the newest prefetches in flight.
 #pragma unroll
-        for (int e = 0; e < 8; e++) zero[e] = (bf16)0.0f;
-#pragma unroll
-        for (int i = 0; i < kSteps; i++) { set_b.tq[i] = zero; set_b.tdo[i] = zero; }
-        set_b.pb[0] = set_b.pb[1] = set_b.dsb[0] = set_b.dsb[1] = zero;
-        if (SPILL) set_a.dsb[0] = set_a.dsb[1] = zero;      // (what the first step of the pass stores when nothing is deferred)
+    for (int kb = 0; kb < D / 16; kb++) {
+        // (D = 128: into the accumulator half of the register file, from where the matrix instructions read
+        // them just as well; that leaves the other half to the vector ALU's operands, the score blocks among them)
+        if (S::kPipe) asm volatile("" : "+a"(kf[kb]), "+a"(vf[kb]));
+        else asm volatile("" : "+v"(kf[kb]), "+v"(vf[kb]));
     }
-    f32x4 lse4[4], dl4[4];
-    // SPILL: where the dS block held in the previous step's fragment set goes (see step()); at the start of
-    // a pass that set is all zeros and the address is the pass's own first block
-    char* ds_pending = nullptr;
-    if (SPILL) {
-        const size_t q_head = (size_t)(bh / hkv) * hq + (size_t)(bh % hkv) * group;
-        ds_pending = DS + ((q_head * num_kv_tiles + kt) * n_qb + i_begin / S::kTileQ) * (size_t)8192 + wave * 2048;
-    }
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();           // the pass's first blocks landed and visible
+    __builtin_amdgcn_sched_barrier(0);
+
+    // register r of a score block <-> query i0 + 8*(r/4) + 4h + r%4, lane <-> key my_j
+    const bool pad_key = TAIL && SPILL && my_j >= Nk;    // a padding key was computed from the last real row: its dS must not reach dQ
+    auto q_head_of = [&](int g) { return (size_t)(bh / hkv) * hq + (size_t)(bh % hkv) * group + g; };
+
+    if constexpr (S::kPipe) {
+    // ------------------------------------------------------------------------------------------
+    // D = 128: one wave per SIMD.  A wave issues in order, at most one instruction every four cycles,
+    // and a matrix instruction holds the matrix pipe for 32: with matrix instructions back to back the
+    // wave idles until the pipe frees, and the ~150 vector instructions of a block then run with the
+    // pipe idle.  So every matrix instruction here is followed by the handful of other instructions
+    // that fit in its shadow, and the work of three consecutive blocks is in flight at once:
+    //     step n, first half    S, dP of block n+1 (16 MFMAs)  next to  P, dS of block n (vector ALU) and
+    //                           the transposing LDS reads of block n's Q^T, dO^T fragments
+    //     step n, second half   dV^T, dK^T of block n (16 MFMAs)  next to  the LDS reads of the statistics
+    //                           of block n+1 and of the row fragments of block n+2, the dS stores and the prefetch
+    // S and dP exist twice: the matrix pipe writes one copy (accumulator registers) in the first half, the
+    // second half moves it, two registers per MFMA, to the copy the vector ALU reads in the next step.  The empty asm statements keep each group in program order: the compiler keeps them in
+    // order with each other and with the scheduling barriers, and each one names a value that the
+    // instructions of its group produce or consume.
+    // ------------------------------------------------------------------------------------------
+    bf16x8 rq[kSteps], rdo[kSteps];         // row fragments: operands of the next S, dP
+    bf16x8 tq[kSteps], tdo[kSteps];         // transposed fragments [ks * (D/32) + db]: operands of the next dV^T, dK^T
+    bf16x8 pb[2], dsb[2];                   // bf16 P, dS of the block in hand
+    f32x4 lse4[4], dl4[4];                  // statistics of the block whose P, dS come next
+    f32x16 s_acc, dp_acc;                   // S, dP as the matrix pipe leaves them
+    float sc[16], dc[16];                   // ... and where the vector ALU reads them one step later
 
     auto read_rows = [&](const char* qs, int kb) {
         rq[kb] = lds_read_b128(qs, row_lane ^ ((2 * kb) << 4));
         rdo[kb] = lds_read_b128(qs + S::kQTileBytes, row_lane ^ ((2 * kb) << 4));
     };
-    auto read_transposed = [&](Late& L, const char* qs, int idx) {
+    auto read_tq = [&](const char* qs, int idx) {
+        const int ks = idx / (D / 32), db = idx % (D / 32);
+        const int row_off = 16 * ks * S::kRowBytes;
+        const int x0 = (4 * db) << 4, x1 = ((4 * db) ^ 2) << 4;
+        tq[idx] = concat(lds_read_tr16(qs, (trq_lane ^ x0) + row_off),
+                         lds_read_tr16(qs, (trq_lane ^ x1) + row_off + 8 * S::kRowBytes));
+    };
+    auto read_tdo = [&](const char* qs, int idx) {
         const int ks = idx / (D / 32), db = idx % (D / 32);
         const int row_off = 16 * ks * S::kRowBytes;
         const int x0 = (4 * db) << 4, x1 = ((4 * db) ^ 2) << 4;
         const char* dos = qs + S::kQTileBytes;
-        L.tdo[idx] = concat(lds_read_tr16(dos, (trq_lane ^ x0) + row_off),
-                            lds_read_tr16(dos, (trq_lane ^ x1) + row_off + 8 * S::kRowBytes));
-        L.tq[idx] = concat(lds_read_tr16(qs, (trq_lane ^ x0) + row_off),
-                           lds_read_tr16(qs, (trq_lane ^ x1) + row_off + 8 * S::kRowBytes));
+        tdo[idx] = concat(lds_read_tr16(dos, (trq_lane ^ x0) + row_off),
+                          lds_read_tr16(dos, (trq_lane ^ x1) + row_off + 8 * S::kRowBytes));
     };
-    auto late_products = [&](const Late& L, int idx) {
-        const int ks = idx / (D / 32), db = idx % (D / 32);
-        dv_acc[db] = mfma32(L.tdo[idx], L.pb[ks], dv_acc[db]);
-        dk_acc[db] = mfma32(L.tq[idx], L.dsb[ks], dk_acc[db]);
+    // S, dP of the block whose row fragments are in rq / rdo; `between(kb, which)` runs after each MFMA
+    auto scores = [&](f32x16& s_out, f32x16& dp_out, auto between) {
+#pragma unroll
+        for (int kb = 0; kb < kSteps; kb++) {
+            if (kb == 0) {
+                f32x16 zero;
+#pragma unroll
+                for (int r = 0; r < 16; r++) zero[r] = 0.f;
+                asm volatile("" : "+v"(rq[0]));
+                s_out = mfma32(rq[0], kf[0], zero);
+                asm volatile("" : "+a"(s_out));
+                between(kb, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("" : "+v"(rdo[0]));
+                dp_out = mfma32(rdo[0], vf[0], zero);
+                asm volatile("" : "+a"(dp_out));
+                between(kb, 1);
+                __builtin_amdgcn_sched_barrier(0);
+            } else {
+                asm volatile("" : "+a"(s_out));
+                s_out = mfma32(rq[kb], kf[kb], s_out);
+                asm volatile("" : "+a"(s_out));
+                between(kb, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("" : "+a"(dp_out));
+                dp_out = mfma32(rdo[kb], vf[kb], dp_out);
+                asm volatile("" : "+a"(dp_out));
+                between(kb, 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
     };
 
-    // Every global load so far (this pass's K, V fragments, its first blocks, the previous pass's
-    // stores) completes here.  The empty asm statements pin the fragment loads above this point (the
-    // compiler would otherwise sink them to their first use inside the loop and wait for them there,
-    // draining the prefetch every iteration): inside the loop the only waits on the vector memory
-    // counter are the explicit ones, which leave the newest prefetch in flight.
+    // ---- start of the pass: S, dP of its first block; its statistics and the second block's row
+    // fragments are read meanwhile.  (The previous pass computed scores for this block too, with its own
+    // K and V: they are dropped.)
+    {
+        const char* q0s = ring + c_stage;
+        const char* q1s = ring + next_stage(c_stage);
+        const f32x4* stat0 = (const f32x4*)(q0s + 2 * S::kQTileBytes);
 #pragma unroll
-    for (int kb = 0; kb < D / 16; kb++) asm volatile("" : "+v"(kf[kb]), "+v"(vf[kb]));
-    wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();           // the pass's first blocks landed and visible
-    __builtin_amdgcn_sched_barrier(0);
+        for (int kb = 0; kb < kSteps; kb++) read_rows(q0s, kb);
+        __builtin_amdgcn_sched_barrier(0);
+        scores(s_acc, dp_acc, [&](int kb, int which) {
+            if (kb < 4) {
+                if (which == 0) lse4[kb] = stat0[2 * kb + h];
+                else dl4[kb] = stat0[8 + 2 * kb + h];
+            }
+        });
 #pragma unroll
-    for (int kb = 0; kb < kSteps; kb++) read_rows(ring + (c_count & (S::kStages - 1)) * S::kStageBytes, kb);
+        for (int kb = 0; kb < kSteps; kb++) read_rows(q1s, kb);
+#pragma unroll
+        for (int r = 0; r < 16; r++) { sc[r] = s_acc[r]; dc[r] = dp_acc[r]; }
+        __builtin_amdgcn_sched_barrier(0);
+    }
 
-    // One query block.  cur receives this block's transposed fragments and bf16 P / dS; prev holds
-    // those of the previous block, whose dV^T / dK^T products run here, interleaved with this block's
-    // vector-ALU work (P, dS), so that the matrix pipe has work while the ALU is busy.
-    auto step = [&](auto masked, int blk, Late& cur, const Late& prev, char* ds_head) {
+    auto step = [&](auto masked, int blk, char* ds_head) {
         const int i0 = i_begin + blk * S::kTileQ;
-        const char* qs = ring + ((c_count + blk) & (S::kStages - 1)) * S::kStageBytes;
-        const char* qs_next = ring + ((c_count + blk + 1) & (S::kStages - 1)) * S::kStageBytes;
+        const int st1 = next_stage(c_stage), st2 = next_stage(st1);
+        const char* q0s = ring + c_stage;           // block n
+        const char* q1s = ring + st1;               // block n+1
+        const char* q2s = ring + st2;               // block n+2
+        const f32x4* stat1 = (const f32x4*)(q1s + 2 * S::kQTileBytes);
+        c_stage = st1;
+
+        // ---- first half.  After each MFMA of the next block's S, dP: one element of P and dS - the
+        // exponential of element r is started in one group and used in the next, so that nothing waits
+        // for it - and the transposing reads of one operand of the second half.
+        float pe[16], de[16], te[16];
+        auto element_start = [&](int r) {
+            const int g = r >> 2, t = r & 3;
+            float sv = sc[r], dv = dc[r];
+            asm volatile("" : "+v"(sv), "+v"(dv));
+            if (decltype(masked)::value && i0 + 8 * g + 4 * h + t + off < my_j) sv = -INFINITY;
+            if (pad_key) sv = -INFINITY;
+            pe[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv, c, -lse4[g][t] * kLog2e));
+            te[r] = dv - dl4[g][t];
+            asm volatile("" : "+v"(pe[r]), "+v"(te[r]));
+        };
+        auto element_finish = [&](int r) {
+            de[r] = pe[r] * te[r];
+            asm volatile("" : "+v"(de[r]));
+        };
+        scores(s_acc, dp_acc, [&](int kb, int which) {
+            const int r = 2 * kb + which;
+            element_start(r);
+            if (r > 0) element_finish(r - 1);
+            if (which == 0) read_tdo(q0s, kb); else read_tq(q0s, kb);
+            if (kb == kSteps / 2 + 1) {          // (elements 0..8 are done)
+                if (which == 0) {
+                    pb[0] = cvt8(pe[0], pe[1], pe[2], pe[3], pe[4], pe[5], pe[6], pe[7]);
+                    asm volatile("" : "+v"(pb[0]));
+                } else {
+                    dsb[0] = cvt8(de[0], de[1], de[2], de[3], de[4], de[5], de[6], de[7]);
+                    asm volatile("" : "+v"(dsb[0]));
+                }
+            }
+        });
+
+        // ---- second half: the products of this block, next to the reads of the next blocks' fragments
+        element_finish(15);
+        // group g of 16 moves two registers of the next block's scores: S first (its last MFMA was issued before dP's)
+        auto move_scores = [&](int g) {
+            const int r = 2 * (g & 7);
+            float a = g < 8 ? s_acc[r] : dp_acc[r], b = g < 8 ? s_acc[r + 1] : dp_acc[r + 1];
+            asm volatile("" : "+v"(a), "+v"(b));
+            if (g < 8) { sc[r] = a; sc[r + 1] = b; } else { dc[r] = a; dc[r + 1] = b; }
+        };
+#pragma unroll
+        for (int idx = 0; idx < kSteps; idx++) {
+            const int ks = idx / (D / 32), db = idx % (D / 32);
+            if (idx == 0) {                  // the second half of P, dS is not needed before idx = kSteps / 2
+                pb[1] = cvt8(pe[8], pe[9], pe[10], pe[11], pe[12], pe[13], pe[14], pe[15]);
+                dsb[1] = cvt8(de[8], de[9], de[10], de[11], de[12], de[13], de[14], de[15]);
+            }
+            asm volatile("" : "+a"(dv_acc[db]));
+            dv_acc[db] = mfma32(tdo[idx], pb[ks], dv_acc[db]);
+            asm volatile("" : "+a"(dv_acc[db]));
+            rq[idx] = lds_read_b128(q2s, row_lane ^ ((2 * idx) << 4));
+            if (idx < 4) lse4[idx] = stat1[2 * idx + h];
+            if (idx == 0) asm volatile("" : "+v"(pb[1]), "+v"(dsb[1]));
+            if (idx == 0) prepare();         // block n+6 goes into the stage of block n-1, which every wave has left
+            if (idx == S::kLoadsPerBlock + 1) emit(S::kLoadsPerBlock);
+            move_scores(2 * idx);
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("" : "+a"(dk_acc[db]));
+            dk_acc[db] = mfma32(tq[idx], dsb[ks], dk_acc[db]);
+            asm volatile("" : "+a"(dk_acc[db]));
+            rdo[idx] = lds_read_b128(q2s + S::kQTileBytes, row_lane ^ ((2 * idx) << 4));
+            if (idx < 4) dl4[idx] = stat1[8 + 2 * idx + h];
+            if (idx >= 1 && idx <= S::kLoadsPerBlock) emit(idx - 1);
+            if (SPILL && idx == kSteps / 2 + 2) {       // (both halves of dS exist; every step issues exactly these two stores)
+                char* dst = ds_head + ((size_t)(i0 / S::kTileQ) * 4 + wave) * 2048 + lane * 16;
+                *(bf16x8*)dst = dsb[0];
+                *(bf16x8*)(dst + 1024) = dsb[1];
+            }
+            move_scores(2 * idx + 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        // Block n+3 (issued three steps ago) must have landed before the next step reads it; the newer
+        // prefetches stay in flight, and so do the dS stores issued since: the counter retires loads and stores in issue order, and the stores of the last
+        // four steps are younger than the loads waited for.  The wave's own LDS reads must have
+        // returned as well: after the barrier the next step's prefetch overwrites the stage of block n.
+        constexpr int kStores = SPILL ? 8 : 0;
+        prepare_turn();
+        wait_vmcnt_lds_done<3 * (S::kLoadsPerBlock + 1) + kStores>();
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // When causal, the first n_masked blocks of every query head are the ones that may touch the
+    // diagonal.  The stream runs on across the heads of the group.
+#pragma unroll 1
+    for (int g = 0; g < group; g++) {
+        // dS blocks of (this query head, this key tile); query block 0 = queries 0..31 of the head
+        char* ds_head = SPILL ? DS + ((q_head_of(g) * num_kv_tiles + kt) * n_qb) * (size_t)8192 : nullptr;
+        int blk = 0;
+        if (CAUSAL) {
+#pragma unroll 1
+            for (; blk < n_masked; blk++) step(std::true_type{}, blk, ds_head);
+        }
+#pragma unroll 1
+        for (; blk < n_blocks; blk++) step(std::false_type{}, blk, ds_head);
+    }
+    } else {
+    // ------------------------------------------------------------------------------------------
+    // D = 64: the registers allow two workgroups per compute unit, i.e. two waves per SIMD that fill
+    // each other's gaps; the phases of a block run one after the other.
+    // ------------------------------------------------------------------------------------------
+    bf16x8 rq[kSteps], rdo[kSteps];         // row fragments of the block about to be computed
+    bf16x8 tq[kSteps], tdo[kSteps], pb[2], dsb[2];      // transposed fragments [ks * (D/32) + db] and bf16 P / dS of a block
+    f32x4 lse4[4], dl4[4];
+
+    auto read_rows = [&](const char* qs, int kb) {
+        rq[kb] = lds_read_b128(qs, row_lane ^ ((2 * kb) << 4));
+        rdo[kb] = lds_read_b128(qs + S::kQTileBytes, row_lane ^ ((2 * kb) << 4));
+    };
+    auto read_transposed = [&](const char* qs, int idx) {
+        const int ks = idx / (D / 32), db = idx % (D / 32);
+        const int row_off = 16 * ks * S::kRowBytes;
+        const int x0 = (4 * db) << 4, x1 = ((4 * db) ^ 2) << 4;
+        const char* dos = qs + S::kQTileBytes;
+        tdo[idx] = concat(lds_read_tr16(dos, (trq_lane ^ x0) + row_off),
+                          lds_read_tr16(dos, (trq_lane ^ x1) + row_off + 8 * S::kRowBytes));
+        tq[idx] = concat(lds_read_tr16(qs, (trq_lane ^ x0) + row_off),
+                         lds_read_tr16(qs, (trq_lane ^ x1) + row_off + 8 * S::kRowBytes));
+    };
+#pragma unroll
+    for (int kb = 0; kb < kSteps; kb++) read_rows(ring + c_stage, kb);
+
+    auto step = [&](auto masked, int blk, char* ds_head) {
+        const int i0 = i_begin + blk * S::kTileQ;
+        const char* qs = ring + c_stage;
+        c_stage = next_stage(c_stage);
+        const char* qs_next = ring + c_stage;
         const f32x4* stat = (const f32x4*)(qs + 2 * S::kQTileBytes);
 
         issue_next();                       // into the stage of the previous block, which every wave has left
@@ -401,35 +615,20 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         for (int kb = 0; kb < kSteps; kb++) {
             s = mfma32(rq[kb], kf[kb], s);
             dp = mfma32(rdo[kb], vf[kb], dp);
-            read_transposed(cur, qs, kb);
+            read_transposed(qs, kb);
             if (kb < 4) { lse4[kb] = stat[2 * kb + h]; dl4[kb] = stat[8 + 2 * kb + h]; }
             __builtin_amdgcn_sched_barrier(0);
         }
-        // SPILL: the PREVIOUS block's dS leaves here, one step after it was formed (stored right after its
-        // conversion it costs ~10 % more cycles per step: every score of the block has to be finished first).
-        // Every step issues exactly these two stores - the waits below count them; the first step of a pass
-        // writes the zeros of the fresh fragment set to its own block, which the next step overwrites.
-        if (SPILL) {
-            *(bf16x8*)(ds_pending + lane * 16) = prev.dsb[0];
-            *(bf16x8*)(ds_pending + 1024 + lane * 16) = prev.dsb[1];
-            ds_pending = ds_head + ((size_t)(i0 / S::kTileQ) * 4 + wave) * 2048;     // this block (wave-uniform)
-            __builtin_amdgcn_sched_barrier(0);
-        }
 
-        // ---- phase 2 (this block's P, dS) interleaved with phase 3 of the PREVIOUS block
-        // (dV^T += dO^T P, dK^T += Q^T dS) and with the reads of the next block's row fragments
-        // (that block landed before the barrier that ended the previous iteration).
-        // register r <-> query i0 + 8*(r/4) + 4h + r%4, lane <-> key my_j
-        // Only the first four blocks of a causal tile touch the diagonal: they run as a loop of
-        // their own that pushes the masked scores to -inf (P = 2^-inf = 0), so that the main loop
-        // carries no compare / select per element.
+        // ---- phase 2: P, dS.  Only the first blocks of a causal tile touch the diagonal: they run as a
+        // loop of their own that pushes the masked scores to -inf (P = 2^-inf = 0), so that the main
+        // loop carries no compare / select per element.
         if (decltype(masked)::value) {
 #pragma unroll
             for (int r = 0; r < 16; r++)
                 if (i0 + 8 * (r >> 2) + 4 * h + (r & 3) + off < my_j) s[r] = -INFINITY;
         }
-        // a padding key (row >= Nk) was computed from the last real row: its dS must not reach dQ
-        if (TAIL && SPILL && my_j >= Nk) {
+        if (pad_key) {
 #pragma unroll
             for (int r = 0; r < 16; r++) s[r] = -INFINITY;
         }
@@ -446,70 +645,50 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
 #pragma unroll
         for (int ks = 0; ks < 2; ks++) {
             const int r0 = 8 * ks;
-            cur.pb[ks] = cvt8(s[r0], s[r0 + 1], s[r0 + 2], s[r0 + 3], s[r0 + 4], s[r0 + 5], s[r0 + 6], s[r0 + 7]);
-            cur.dsb[ks] = cvt8(dp[r0], dp[r0 + 1], dp[r0 + 2], dp[r0 + 3], dp[r0 + 4], dp[r0 + 5], dp[r0 + 6], dp[r0 + 7]);
+            pb[ks] = cvt8(s[r0], s[r0 + 1], s[r0 + 2], s[r0 + 3], s[r0 + 4], s[r0 + 5], s[r0 + 6], s[r0 + 7]);
+            dsb[ks] = cvt8(dp[r0], dp[r0 + 1], dp[r0 + 2], dp[r0 + 3], dp[r0 + 4], dp[r0 + 5], dp[r0 + 6], dp[r0 + 7]);
         }
+        // SPILL: every step issues exactly these two stores - the waits below count them
+        if (SPILL) {
+            char* dst = ds_head + ((size_t)(i0 / S::kTileQ) * 4 + wave) * 2048 + lane * 16;
+            *(bf16x8*)dst = dsb[0];
+            *(bf16x8*)(dst + 1024) = dsb[1];
+        }
+
+        // ---- phase 3: dV^T += dO^T P, dK^T += Q^T dS, and the reads of the next block's row fragments
+        // (that block landed before the barrier that ended the previous iteration; the next block in the
+        // stream is the next pass's first one after this pass's last)
 #pragma unroll
         for (int idx = 0; idx < kSteps; idx++) {
-            late_products(prev, idx);
-            read_rows(qs_next, idx);        // (the next block in the stream: the next pass's first one after this pass's last)
-        }
-        // schedule: one MFMA, then a slice of the vector work and one LDS read
-#pragma unroll
-        for (int i = 0; i < 2 * kSteps; i++) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);   // VALU
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+            const int ks = idx / (D / 32), db = idx % (D / 32);
+            dv_acc[db] = mfma32(tdo[idx], pb[ks], dv_acc[db]);
+            dk_acc[db] = mfma32(tq[idx], dsb[ks], dk_acc[db]);
+            read_rows(qs_next, idx);
         }
 
         // the block two ahead in the stream (issued two iterations ago) must have landed before the
-        // next iteration reads its rows; the newer prefetches may stay in flight (wave 0 issues one
-        // more load per block).  The wave's own LDS reads of this block's stage must have returned as
+        // next iteration reads its rows; the newer prefetches may stay in flight.  The wave's own LDS reads of this block's stage must have returned as
         // well: after the barrier the next step's prefetch overwrites that stage.
-        // (the counter retires loads and stores in issue order: the two dS stores of this step and of the
+        // (the counter retires loads and stores in issue order: the dS stores of this step and of the
         // previous one were issued after the loads waited for)
         constexpr int kStores = SPILL ? 4 : 0;
-        if (wave == 0) wait_vmcnt_lds_done<(S::kAhead - 2) * (S::kLoadsPerBlock + 1) + kStores>();
-        else wait_vmcnt_lds_done<(S::kAhead - 2) * S::kLoadsPerBlock + kStores>();
+        wait_vmcnt_lds_done<(S::kAhead - 2) * (S::kLoadsPerBlock + 1) + kStores>();
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // n_blocks and n_masked are even; when causal, the first n_masked blocks of every query head are
-    // the ones that may touch the diagonal.  The deferred products run on across the heads of the group.
 #pragma unroll 1
     for (int g = 0; g < group; g++) {
-        // dS blocks of (this query head, this key tile); query block 0 = queries 0..31 of the head
-        char* ds_head = nullptr;
-        if (SPILL) {
-            const size_t q_head = (size_t)(bh / hkv) * hq + (size_t)(bh % hkv) * group + g;
-            ds_head = DS + ((q_head * num_kv_tiles + kt) * n_qb) * (size_t)8192;
-        }
+        char* ds_head = SPILL ? DS + ((q_head_of(g) * num_kv_tiles + kt) * n_qb) * (size_t)8192 : nullptr;
         int blk = 0;
         if (CAUSAL) {
 #pragma unroll 1
-            for (; blk < n_masked; blk += 2) {
-                if (kDeferred) {
-                    step(std::true_type{}, blk, set_a, set_b, ds_head);
-                    step(std::true_type{}, blk + 1, set_b, set_a, ds_head);
-                } else {
-                    step(std::true_type{}, blk, set_a, set_a, ds_head);
-                    step(std::true_type{}, blk + 1, set_a, set_a, ds_head);
-                }
-            }
+            for (; blk < n_masked; blk++) step(std::true_type{}, blk, ds_head);
         }
 #pragma unroll 1
-        for (; blk < n_blocks; blk += 2) {
-            if (kDeferred) {
-                step(std::false_type{}, blk, set_a, set_b, ds_head);
-                step(std::false_type{}, blk + 1, set_b, set_a, ds_head);
-            } else {
-                step(std::false_type{}, blk, set_a, set_a, ds_head);
-                step(std::false_type{}, blk + 1, set_a, set_a, ds_head);
-            }
-        }
-        c_count += n_blocks;
+        for (; blk < n_blocks; blk++) step(std::false_type{}, blk, ds_head);
+    }
     }
 
     // The next pass's K, V fragments are requested now, so that they travel while this pass's last
@@ -520,18 +699,6 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         pass_tile(c_vu, c_half, nbh, nkt);
         load_kv(nbh, nkt);
     }
-    // the last block's dV^T / dK^T products
-    if (kDeferred) {
-#pragma unroll
-        for (int idx = 0; idx < kSteps; idx++) late_products(set_b, idx);
-    }
-    // ... and its dS (the block count of a pass is even: the last step wrote set_b, or set_a when nothing is deferred)
-    if (SPILL) {
-        const Late& last = kDeferred ? set_b : set_a;
-        *(bf16x8*)(ds_pending + lane * 16) = last.dsb[0];
-        *(bf16x8*)(ds_pending + 1024 + lane * 16) = last.dsb[1];
-    }
-
     // ---- epilogue.  In accumulator layout a lane holds 4 consecutive columns of ONE key row
     // (lane <-> key my_j, register r of block db <-> column 32db + 8*(r/4) + 4h + r%4), so storing
     // from there would touch 32 rows per instruction.  Each wave instead turns its 32 x D tile

@@ -64,6 +64,17 @@ __device__ __forceinline__ void load_global_to_lds16_untracked(const void* gptr,
                  : "m0", "memory");   // "memory": LDS contents change behind the compiler's back
 }
 
+// The same load by lanes 0..15 only (256 bytes); the other lanes are masked off for the one instruction.
+// Call it with every lane active: it restores the execution mask it found.
+__device__ __forceinline__ void load_global_to_lds16_lanes16_untracked(const void* gptr, const char* lds_wave_base) {
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(TK_LDS const char*)lds_wave_base;
+    uint64_t saved;
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 0xffff\n\ts_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b64 exec, %0"
+                 : "=&s"(saved)
+                 : "s"(lds_addr), "v"(gptr)
+                 : "m0", "memory");
+}
+
 // 4 bytes per lane, same rules: LDS address = wave base + 4 * lane.  For rows of fp32 statistics,
 // whose global address is only 4-byte aligned when N is not a multiple of 4.
 __device__ __forceinline__ void load_global_to_lds4_untracked(const void* gptr, const char* lds_wave_base) {
