@@ -28,8 +28,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (published: 2.5 PFLOP/s)
 # reads in the same run; the files under profiles/ give the commands and the raw counters).  The
 # live run cannot collect counters itself, so other workloads report null.
 MEASURED_TRAFFIC = {
-    "fwdbwd_causal_b16_h16_n4096_d128/recompute": {"kernel": "attn_bwd_dkdv_kernel", "bytes": 1.245e9 + 0.537e9,
+    "fwdbwd_causal_b16_h16_n4096_d128": {"kernel": "attn_bwd_dkdv_kernel", "bytes": 1.802e9 + 4.966e9,      # (the form that stores dS)
                                          "source": "profiles/bench_fwdbwd_causal_b16_h16_n4096_d128.txt"},
+    "fwdbwd_causal_b16_h16_n4096_d64/recompute": {"kernel": "attn_bwd_dkdv_kernel", "bytes": 0.583e9 + 0.268e9,
+                                                  "source": "profiles/bench_fwdbwd_causal_b16_h16_n4096_d64.txt"},
     "gemm_8192x8192x8192": {"kernel": "gemm_kernel", "bytes": 1.61e9 + 0.148e9, "source": "profiles/gemm_8192x8192x8192.txt"},
     "decode_b16_hq32_hkv8_nk8192_d128": {"kernel": "attn_fwd_kernel", "bytes": 537.2e6 + 0.54e6, "source": "profiles/decode_b16_hq32_hkv8_nk8192_d128.txt"},
     "rotary_fwdbwd_causal_b16_h16_n4096_d128": {"kernel": "rotary_kernel", "bytes": 0.270e9 + 0.268e9, "source": "profiles/rotary_b16_h16_n4096_d128.txt"},
@@ -225,9 +227,10 @@ def main():
     ap.add_argument("--op", choices=["attention", "rotary", "gemm", "decode"], default="attention",
                     help="attention (default: the headline fwd+bwd step), the rotary kernel on the same tensor shape, "
                          "the bf16 GEMM (8192^3), or the decode-shaped forward (one query per head, B16 Hq32 Hkv8 Nk8192 D128)")
-    ap.add_argument("--bwd-form", choices=["spill", "recompute"], default="spill",
-                    help="spill (default): tk_attn_bwd gets the large workspace, its dK/dV kernel stores dS and dQ is formed "
-                         "from it (Delta, dK/dV, dQ-from-dS kernels); recompute: Delta-only workspace, dQ kernel recomputes dS")
+    ap.add_argument("--bwd-form", choices=["auto", "spill", "recompute"], default="auto",
+                    help="spill: tk_attn_bwd gets the large workspace, its dK/dV kernel stores dS and dQ is formed "
+                         "from it (Delta, dK/dV, dQ-from-dS kernels); recompute: Delta-only workspace, dQ kernel recomputes dS; "
+                         "auto (default): spill at D = 128, recompute at D = 64 (the faster form of each)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle sample")
     ap.add_argument("--no-mfma-probe", action="store_true", help="skip the bare-MFMA ceiling measurement")
@@ -262,6 +265,8 @@ def main():
     o = torch.empty_like(qd)
     lse = torch.empty((B, H, N), dtype=torch.float32, device=dev)
     dq, dk, dv = torch.empty_like(qd), torch.empty_like(kd), torch.empty_like(vd)
+    if args.bwd_form == "auto":
+        args.bwd_form = "spill" if D == 128 else "recompute"
     spill = args.bwd_form == "spill"
     ws = attn.alloc_bwd_workspace(B, H, N, D, dev, spill=spill)     # allocated once, outside every timed region
     ws_bytes = ws.numel()
