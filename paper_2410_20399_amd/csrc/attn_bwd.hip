@@ -263,14 +263,15 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
         char* base = ring + e_stage;
         if (which < S::kLoadsPerBlock) {        // Q rows, then dO rows
             const int it = which % S::kQLoads;
-            const bf16* src = (which < S::kQLoads ? Q : dO) + e_row * D + q_src[it];
+            const bf16* block = (which < S::kQLoads ? Q : dO) + e_row * D;      // wave-uniform
             char* dst = base + (which < S::kQLoads ? 0 : S::kQTileBytes) + it * (S::kThreads * 16) + wave * 1024;
             if (TAIL) {
                 // a block that runs past the last query: rows >= Nq fetch row Nq-1 instead
                 const int r = e_i0 + (it * S::kThreads + tid) / S::kChunksPerRow;
-                src -= (r < Nq ? 0 : r - (Nq - 1)) * D;
+                load_global_to_lds16_untracked(block + q_src[it] - (r < Nq ? 0 : r - (Nq - 1)) * D, dst);
+            } else {
+                load_global_to_lds16_sbase_untracked(block, (uint32_t)q_src[it] * 2, dst);
             }
-            load_global_to_lds16_untracked(src, dst);
         } else if (TAIL) {
             // The statistics: every wave fetches them, to the same place (the same bytes four times over cost
             // nothing; a branch on the wave number costs every wave a restart of its instruction stream, and
@@ -313,7 +314,8 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     };
 
     int c_vu = blockIdx.x, c_half = 0;      // consumer side: the pass being computed (the grid never exceeds the unit count)
-    int c_stage = 0;                        // byte offset of the ring stage of the next block to consume
+    int c_stage = 0;                        // byte offset of the ring stage of the next block to consume ...
+    int c_stage1 = S::kStageBytes, c_stage2 = 2 * S::kStageBytes;      // ... and of the two blocks after it (D = 128)
     {
         int bh, kt;
         pass_tile(c_vu, c_half, bh, kt);
@@ -443,7 +445,7 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
     // K and V: they are dropped.)
     {
         const char* q0s = ring + c_stage;
-        const char* q1s = ring + next_stage(c_stage);
+        const char* q1s = ring + c_stage1;
         const f32x4* stat0 = (const f32x4*)(q0s + 2 * S::kQTileBytes);
 #pragma unroll
         for (int kb = 0; kb < kSteps; kb++) read_rows(q0s, kb);
@@ -463,12 +465,13 @@ void attn_bwd_dkdv_kernel(const bf16* __restrict__ Q, const bf16* __restrict__ K
 
     auto step = [&](auto masked, int blk, char* ds_head) {
         const int i0 = i_begin + blk * S::kTileQ;
-        const int st1 = next_stage(c_stage), st2 = next_stage(st1);
         const char* q0s = ring + c_stage;           // block n
-        const char* q1s = ring + st1;               // block n+1
-        const char* q2s = ring + st2;               // block n+2
+        const char* q1s = ring + c_stage1;          // block n+1
+        const char* q2s = ring + c_stage2;          // block n+2
         const f32x4* stat1 = (const f32x4*)(q1s + 2 * S::kQTileBytes);
-        c_stage = st1;
+        c_stage = c_stage1;
+        c_stage1 = c_stage2;
+        c_stage2 = next_stage(c_stage2);
 
         // ---- first half.  After each MFMA of the next block's S, dP: one element of P and dS - the
         // exponential of element r is started in one group and used in the next, so that nothing waits

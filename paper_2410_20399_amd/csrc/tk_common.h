@@ -64,6 +64,17 @@ __device__ __forceinline__ void load_global_to_lds16_untracked(const void* gptr,
                  : "m0", "memory");   // "memory": LDS contents change behind the compiler's back
 }
 
+// The same load with the address split into a wave-uniform base (scalar registers) and a 32-bit byte offset per
+// lane: no 64-bit vector add per load.
+__device__ __forceinline__ void load_global_to_lds16_sbase_untracked(const void* uniform_base, uint32_t lane_byte_off,
+                                                                     const char* lds_wave_base) {
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(TK_LDS const char*)lds_wave_base;
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(lane_byte_off), "s"(uniform_base)
+                 : "m0", "memory");
+}
+
 // The same load by lanes 0..15 only (256 bytes); the other lanes are masked off for the one instruction.
 // Call it with every lane active: it restores the execution mask it found.
 __device__ __forceinline__ void load_global_to_lds16_lanes16_untracked(const void* gptr, const char* lds_wave_base) {
