@@ -104,16 +104,18 @@ template <int D> __device__ __forceinline__ int swz(int row) {
 }
 
 // At D = 128: one wave per SIMD (the dK^T, dV^T accumulators and the K, V fragments take 192
-// registers), so nothing hides LDS latency but the schedule itself.  At D = 64 the registers allow
-// two workgroups per compute unit, i.e. two waves per SIMD that fill each other's gaps (the
-// vector work per MFMA is twice that of D = 128 there).  Every MFMA operand is read one phase
-// ahead of its use:
+// registers), so nothing hides LDS latency or fills the vector ALU but the schedule itself: the
+// pipelined step described inside the kernel, with the query blocks arriving by direct global->LDS
+// loads issued six blocks ahead into a seven-stage ring.
+// At D = 64 the registers allow two workgroups per compute unit, i.e. two waves per SIMD that fill
+// each other's gaps (the vector work per MFMA is twice that of D = 128 there), and the phases of a
+// block run one after the other, every MFMA operand read one phase ahead of its use:
 //     phase 1  S, dP MFMAs from row fragments already in registers; meanwhile the transposed
 //              fragments (dO^T, Q^T) and the statistics of THIS block are read from LDS
 //     phase 2  P, dS on the vector ALU
 //     phase 3  dV^T, dK^T MFMAs from the transposed fragments; meanwhile the row fragments of the
 //              NEXT block are read from LDS
-// and the query blocks themselves arrive by direct global->LDS loads issued three blocks ahead.
+// with the query blocks issued three blocks ahead into a four-stage ring.
 //
 // Nothing hides a workgroup's start-up and wind-down either, so the launch is persistent: the
 // resident workgroups (one per compute unit, two at D = 64) walk the key tiles v = blockIdx.x, blockIdx.x + gridDim.x, ... and
