@@ -214,6 +214,34 @@ def test_dq_stage_with_delta_folded_in(attn, B, Hq, Hkv, N, D, causal):
     assert relf(f64(dq.cpu()), f64(dq3.cpu())) <= 1e-3
 
 
+GUARD = 1024      # bytes of padding after the dS buffer, filled with a sentinel
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,N,D,causal", [(2, 4, 4, 384, 128, True), (1, 8, 2, 640, 128, False), (2, 4, 2, 333, 128, True),
+                                                 (1, 4, 4, 512, 64, True), (1, 6, 3, 200, 64, False)])
+def test_storing_stages_equal_the_call(attn, B, Hq, Hkv, N, D, causal):
+    """tk_attn_bwd with the large workspace runs tk_attn_bwd_delta, tk_attn_bwd_dkdv_ds and tk_attn_bwd_dq_from_ds:
+    the three stage entry points, called one after the other on a dS buffer of their own, give the same bits."""
+    g = torch.Generator().manual_seed(5151 + N + D)
+    q, d_o = (torch.randn(B, Hq, N, D, generator=g).to(torch.bfloat16).cuda() for _ in range(2))
+    k, v = (torch.randn(B, Hkv, N, D, generator=g).to(torch.bfloat16).cuda() for _ in range(2))
+    scale = 1 / math.sqrt(D)
+    print(f"launch storing stages B{B} Hq{Hq} Hkv{Hkv} N{N} D{D} causal={causal}", flush=True)
+    o, lse = attn.gqa_fwd(q, k, v, causal, scale)
+    ws = attn.alloc_bwd_workspace(B, Hq, N, D, spill=True)
+    dq, dk, dv = attn.gqa_bwd(q, k, v, o, d_o, lse, causal, scale, ws)
+    delta = attn.attn_bwd_delta(o, d_o)
+    n_ds = attn.tk_attn_bwd_ds_bytes(B, Hq, N, N, D)
+    assert n_ds > 0
+    ds = torch.full((n_ds + GUARD,), 0x5A, dtype=torch.uint8, device="cuda")       # stale contents must not matter
+    dq2, dk2, dv2 = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    assert attn.tk_attn_bwd_dkdv_ds(q, k, v, d_o, lse, delta, dk2, dv2, ds, B, Hq, Hkv, N, D, causal, scale) == attn.TK_OK
+    assert attn.tk_attn_bwd_dq_from_ds(k, ds, dq2, B, Hq, Hkv, N, D, causal, scale) == attn.TK_OK
+    torch.cuda.synchronize()
+    assert bool((ds[-GUARD:] == 0x5A).all()), "wrote past the end of the dS buffer"
+    assert torch.equal(dq, dq2) and torch.equal(dk, dk2) and torch.equal(dv, dv2)
+
+
 # ------------------------------------------------------------------ degenerate and stress cases
 def test_zero_queries_uniform_attention(attn):
     """Q = 0 -> P uniform: O_i = mean of V (non-causal) or running mean (causal), LSE = ln(#keys)."""
